@@ -1,0 +1,212 @@
+"""ctypes front end of the CPU oracle (oracle/netmax_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  The product package never imports it.  All
+arguments are numpy arrays on the host; nothing here touches a GPU.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "netmax_oracle.c")
+_LIB = os.path.join(_DIR, "libnetmax_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (generic x86-64 code, no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_LIB)
+        L.ora_set_threads.restype = C.c_int
+        L.ora_thresholds.restype = C.c_int
+        L.ora_peer_of_word.restype = C.c_int32
+        L.ora_grad_mlp.restype = C.c_double
+        L.ora_consensus_dist.restype = C.c_double
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a: np.ndarray, dtype, *shape_opts) -> np.ndarray:
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags.c_contiguous, (a.dtype, dtype)
+    return a
+
+
+def set_threads(n: int) -> int:
+    return int(lib().ora_set_threads(C.c_int(n)))
+
+
+def philox4x32_10(ctr: Sequence[int], key: Sequence[int]) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    lib().ora_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def thresholds(P: np.ndarray):
+    """-> (T uint32 [M,M], last int32 [M]); raises ValueError on an invalid row."""
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    M = P.shape[0]
+    T = np.empty((M, M), dtype=np.uint32)
+    last = np.empty(M, dtype=np.int32)
+    if lib().ora_thresholds(C.c_int(M), _p(P), _p(T), _p(last)) != 0:
+        raise ValueError("invalid policy matrix")
+    return T, last
+
+
+def peer_of_word(Trow: np.ndarray, last: int, u: int) -> int:
+    Trow = _chk(Trow, np.uint32)
+    return int(lib().ora_peer_of_word(C.c_int(Trow.shape[0]), _p(Trow), C.c_int32(last), C.c_uint32(u)))
+
+
+def sample_peers(T: np.ndarray, last: np.ndarray, seed: int, it: int) -> np.ndarray:
+    M = T.shape[0]
+    peer = np.empty(M, dtype=np.int32)
+    lib().ora_sample_peers(C.c_int(M), _p(_chk(T, np.uint32)), _p(_chk(last, np.int32)),
+                           C.c_uint64(seed), C.c_uint64(it), _p(peer))
+    return peer
+
+
+def mix_weights(P: np.ndarray, adj: Optional[np.ndarray], alpha: float, rho: float) -> np.ndarray:
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    M = P.shape[0]
+    if adj is not None:
+        adj = np.ascontiguousarray(adj, dtype=np.uint8)
+    w = np.empty((M, M), dtype=np.float64)
+    lib().ora_mix_weights(C.c_int(M), _p(P), _p(adj), C.c_double(alpha), C.c_double(rho), _p(w))
+    return w
+
+
+def sample_batch(M: int, B: int, shard_off: np.ndarray, seed: int, it: int) -> np.ndarray:
+    idx = np.empty((M, B), dtype=np.int32)
+    lib().ora_sample_batch(C.c_int(M), C.c_int(B), _p(_chk(shard_off, np.int64)),
+                           C.c_uint64(seed), C.c_uint64(it), _p(idx))
+    return idx
+
+
+def synth_grad(M: int, D: int, ld: int, sigma: float, seed: int, it: int,
+               out: Optional[np.ndarray] = None) -> np.ndarray:
+    G = np.empty((M, ld), dtype=np.float32) if out is None else _chk(out, np.float32)
+    lib().ora_synth_grad(C.c_int(M), C.c_int64(D), C.c_int64(ld), C.c_double(sigma),
+                         C.c_uint64(seed), C.c_uint64(it), _p(G))
+    return G
+
+
+def grad_mlp(dims: Sequence[int], params: np.ndarray, feats: np.ndarray, labels: np.ndarray,
+             idx: np.ndarray):
+    """One worker. feats: float32 or uint16 (bfloat16 bits) [n, dims[0]]. -> (grad float32 [D], loss)."""
+    d = np.asarray(dims, dtype=np.int64)
+    nl = len(dims) - 1
+    Dp = int(sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(nl)))
+    assert params.shape[0] >= Dp
+    bf16 = feats.dtype == np.uint16
+    assert bf16 or feats.dtype == np.float32
+    assert feats.flags.c_contiguous and feats.shape[1] == dims[0]
+    idx = _chk(idx, np.int32)
+    assert idx.min() >= 0 and idx.max() < feats.shape[0]
+    grad = np.empty(Dp, dtype=np.float32)
+    loss = lib().ora_grad_mlp(C.c_int(nl), _p(d), _p(_chk(params, np.float32)), _p(feats), C.c_int(int(bf16)),
+                              _p(_chk(labels, np.int32)), _p(idx), C.c_int(idx.shape[0]), _p(grad))
+    return grad, float(loss)
+
+
+def local_grad(dims: Sequence[int], X: np.ndarray, feats: np.ndarray, labels: np.ndarray,
+               shard_off: np.ndarray, idx: np.ndarray, out: Optional[np.ndarray] = None):
+    """All workers. X, G: float32 [M, ld]; idx int32 [M, B] shard-local. -> (G, loss float64 [M])."""
+    d = np.asarray(dims, dtype=np.int64)
+    M, ld = X.shape
+    bf16 = feats.dtype == np.uint16
+    assert bf16 or feats.dtype == np.float32
+    assert feats.flags.c_contiguous and feats.shape[1] == dims[0]
+    G = np.empty_like(X) if out is None else _chk(out, np.float32)
+    loss = np.empty(M, dtype=np.float64)
+    lib().ora_local_grad(C.c_int(M), C.c_int64(ld), C.c_int(len(dims) - 1), _p(d), _p(_chk(X, np.float32)),
+                         _p(feats), C.c_int(int(bf16)), _p(_chk(labels, np.int32)), _p(_chk(shard_off, np.int64)),
+                         _p(_chk(idx, np.int32)), C.c_int(idx.shape[1]), _p(G), _p(loss))
+    return G, loss
+
+
+def mix(Xcur: np.ndarray, G: np.ndarray, V: np.ndarray, peer: np.ndarray, w: np.ndarray,
+        alpha: float, mu: float, wd: float = 0.0, out: Optional[np.ndarray] = None,
+        convex_form: bool = False) -> np.ndarray:
+    """Momentum apply + mix for all workers; V is updated in place; returns x^{t+1}."""
+    M, ld = Xcur.shape
+    Xn = np.empty_like(Xcur) if out is None else _chk(out, np.float32)
+    assert peer.min() >= 0 and peer.max() < M
+    f = lib().ora_mix_convex if convex_form else lib().ora_mix
+    f(C.c_int(M), C.c_int64(ld), _p(_chk(Xcur, np.float32)), _p(_chk(G, np.float32)), _p(_chk(V, np.float32)),
+      _p(Xn), _p(_chk(peer, np.int32)), _p(_chk(w, np.float64)), C.c_double(alpha), C.c_double(mu), C.c_double(wd))
+    return Xn
+
+
+def consensus_dist(X: np.ndarray, D: Optional[int] = None) -> float:
+    M, ld = X.shape
+    return float(lib().ora_consensus_dist(C.c_int(M), C.c_int64(ld if D is None else D), C.c_int64(ld),
+                                          _p(_chk(X, np.float32))))
+
+
+class Oracle:
+    """State machine over the functions above: one instance = M workers of one workload."""
+
+    def __init__(self, *, M, ld, D, dims, batch, lr, momentum, weight_decay, rho, grad_sigma, seed, P,
+                 adj=None, X0, feats=None, labels=None, shard_off=None):
+        self.M, self.ld, self.D, self.dims, self.batch = M, ld, D, tuple(dims), batch
+        self.lr, self.mu, self.wd, self.sigma, self.seed = float(lr), float(momentum), float(weight_decay), float(grad_sigma), int(seed)
+        self.adj = adj
+        self.set_policy(P, rho)
+        self.X = np.array(X0, dtype=np.float32, copy=True)
+        self.Xn = np.empty_like(self.X)
+        self.V = np.zeros_like(self.X)
+        self.G = np.zeros_like(self.X)
+        self.feats, self.labels, self.shard_off = feats, labels, shard_off
+        self.loss = None
+
+    def set_policy(self, P, rho):
+        self.P, self.rho = np.ascontiguousarray(P, dtype=np.float64), float(rho)
+        self.T, self.last = thresholds(self.P)
+        self.w = mix_weights(self.P, self.adj, self.lr, self.rho)
+
+    def sample_peers(self, it):
+        return sample_peers(self.T, self.last, self.seed, it)
+
+    def local_step(self, it):
+        if len(self.dims) == 0:
+            synth_grad(self.M, self.D, self.ld, self.sigma, self.seed, it, out=self.G)
+        else:
+            idx = sample_batch(self.M, self.batch, self.shard_off, self.seed, it)
+            _, self.loss = local_grad(self.dims, self.X, self.feats, self.labels, self.shard_off, idx, out=self.G)
+        return self.G
+
+    def mix(self, peer):
+        mix(self.X, self.G, self.V, peer, self.w, self.lr, self.mu, self.wd, out=self.Xn)
+        self.X, self.Xn = self.Xn, self.X
+        return self.X
+
+    def step(self, it):
+        peer = self.sample_peers(it)
+        self.local_step(it)
+        self.mix(peer)
+        return peer
+
+    def consensus_dist(self):
+        return consensus_dist(self.X, self.D)
