@@ -1,0 +1,158 @@
+/*
+ * netmax.h - C ABI of the MI355X (gfx950) NetMax iteration library.
+ *
+ * One NetMax iteration (arXiv 2009.05766, Algorithm 2 and Section IV,
+ * Eq. (c0)/(c1)) over M worker model copies resident in one GPU's HBM.  For
+ * every worker i, all from the copies of the previous iteration t:
+ *
+ *     m_i       ~ row i of the policy matrix P                (Algorithm 2, peer selection)
+ *     g_i       = grad f(x_i^t ; batch_i^t)                   (Algorithm 2, first-step update)
+ *     v_i^{t+1} = mu v_i^t + g_i + wd x_i^t                   (momentum SGD, Section V-A)
+ *     h_i       = x_i^t - alpha v_i^{t+1}                     (Eq. (c0))
+ *     x_i^{t+1} = h_i - w_i (h_i - x_{m_i}^t)                 (Eq. (c1))
+ *     w_i       = alpha rho (d_{i,m_i} + d_{m_i,i}) / (2 p_{i,m_i}),  0 if m_i = i
+ *
+ * Conventions
+ *   - Plain C.  Every call returns a netmax_status; netmax_last_error() gives the text.
+ *   - "host" pointers are ordinary CPU memory, read during the call only.
+ *     "device" pointers are HIP device memory owned by the caller, who keeps it
+ *     alive while the context uses it.  The library owns only its own tables and
+ *     scratch (thresholds, weights, batch indices, activations, partial sums).
+ *   - Matrices over workers are row-major [M][ld] floats, ld >= D, ld a multiple
+ *     of 64, base pointers 16-byte aligned.  Columns D..ld-1 are padding and stay 0.
+ *   - Kernels are enqueued on the hipStream_t given at init and calls return
+ *     without waiting, except netmax_consensus_dist, netmax_set_policy,
+ *     netmax_set_lr, netmax_get_tables and netmax_destroy, which synchronise
+ *     that stream.
+ *   - The iteration number is an argument: all random draws are counter based
+ *     (Philox4x32-10, key = (seed_lo, seed_hi ^ stream), counter = (block, worker,
+ *     iter_lo, iter_hi)), so any iteration can be replayed.
+ */
+#ifndef NETMAX_H
+#define NETMAX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NETMAX_MAX_LAYERS 7
+
+typedef struct netmax_ctx netmax_ctx; /* opaque, library-owned */
+
+typedef enum {
+    NETMAX_OK = 0,
+    NETMAX_EINVAL = 1,      /* null pointer, M < 2, bad shape, bad alignment, invalid row of P */
+    NETMAX_EINFEASIBLE = 2, /* a selectable pair has mix weight >= 1 (strict mode: >= 1/2, i.e. violates (o3)) */
+    NETMAX_ESTATE = 3,      /* state or data not bound, or call does not fit the model kind */
+    NETMAX_EDEVICE = 4,     /* a HIP call failed */
+    NETMAX_ENOMEM = 5
+} netmax_status;
+
+typedef enum { NETMAX_FLAT = 0, NETMAX_MLP = 1 } netmax_model;
+typedef enum { NETMAX_F32 = 0, NETMAX_BF16 = 1 } netmax_dtype;
+
+typedef struct {
+    int32_t M;         /* workers, 2 .. 4096 */
+    int64_t D;         /* parameters per worker */
+    int64_t ld;        /* row length of X, V, G: >= D, multiple of 64 */
+    int32_t model;     /* netmax_model. FLAT: the local gradient is synthetic N(0, grad_sigma^2) noise.
+                          MLP: ReLU perceptron with softmax cross-entropy; one layer = softmax regression */
+    int32_t n_layers;  /* MLP only: 1 .. NETMAX_MAX_LAYERS */
+    int64_t dims[NETMAX_MAX_LAYERS + 1]; /* MLP only: layer widths, D must equal sum(dims[l]*dims[l+1] + dims[l+1]).
+                          Parameter layout inside a row: per layer W row-major [in][out], then b [out] */
+    int32_t batch;     /* MLP only: samples per worker and iteration, 1 .. 1024 */
+    int32_t gemm_in;   /* netmax_dtype of the feature matrix and of the GEMM operands (accumulation is fp32) */
+    float lr;          /* alpha */
+    float momentum;    /* mu; 0 = plain SGD */
+    float weight_decay;
+    float rho;         /* consensus weight of Eq. (1) */
+    float grad_sigma;  /* FLAT only */
+    uint64_t seed;
+    int32_t strict_o3; /* nonzero: require w < 1/2 for every selectable pair (constraint (o3)) */
+    const double *P;   /* host, M*M row-major; p_im = probability that worker i selects m (Section II-B) */
+    const uint8_t *adj;/* host, M*M neighbourhood indicators d_im, or NULL = complete graph without self loops */
+    void *stream;      /* hipStream_t, NULL = the null stream */
+} netmax_config;
+
+/* Builds the context: validates the configuration, turns P into 32-bit fixed-point cumulative
+ * thresholds (row i: C[m] = round(2^32 sum_{j<=m} p_ij), forced to 2^32 from the last positive
+ * entry on) and the mix-weight table w_im (Algorithm 2, second-step update), uploads both and
+ * allocates the library's scratch.  On failure *out is NULL and netmax_last_error(NULL) has the text.
+ * Rows of P must be non-negative and sum to 1 within 1e-9. */
+int netmax_init(netmax_ctx **out, const netmax_config *cfg);
+
+/* Host-only part of netmax_init, usable without a GPU: validates P (and adj) and writes the tables that
+ * netmax_init would upload.  thresholds_host: uint32 [M][M]; last_host: int32 [M]; w_host: float [M][M];
+ * all host memory owned by the caller.  Returns NETMAX_OK, NETMAX_EINVAL or NETMAX_EINFEASIBLE; the text is
+ * available from netmax_last_error(NULL). */
+int netmax_build_tables(int32_t M, const double *P, const uint8_t *adj, float lr, float rho, int32_t strict_o3,
+                        uint32_t *thresholds_host, int32_t *last_host, float *w_host);
+
+/* A new policy and weight from the monitor takes effect at the next iteration (Algorithm 2, "received
+ * new policy").  P: host, M*M.  The tables are rebuilt; on error the old ones stay in force. */
+int netmax_set_policy(netmax_ctx *ctx, const double *P, float rho);
+
+/* Changes alpha (learning-rate decay, Section V-A) and rebuilds w, which depends on it. */
+int netmax_set_lr(netmax_ctx *ctx, float lr);
+
+/* Binds the caller's state, all device float [M][ld]: x_a holds x^t for the next iteration to run and
+ * x_b receives x^{t+1} (the two swap roles after every netmax_mix); v is the momentum buffer (the caller
+ * zeroes it for v^0 = 0), g receives the gradients. */
+int netmax_bind_state(netmax_ctx *ctx, float *x_a, float *x_b, float *v, float *g);
+
+/* MLP only.  feats: device, [n_total][dims[0]] row-major, float or bfloat16 as cfg.gemm_in says;
+ * labels: device int32 [n_total], values in [0, dims[n_layers]); shard_off: host int64 [M+1], worker i
+ * owns rows shard_off[i] .. shard_off[i+1]-1 (each shard non-empty, at most 2^31-1 rows). */
+int netmax_bind_data(netmax_ctx *ctx, const void *feats, const int32_t *labels, const int64_t *shard_off);
+
+/* Peer selection of Algorithm 2 for all workers at iteration `iter`: worker i draws word 0 of block 0 of
+ * stream 0 and takes the first m whose cumulative threshold exceeds it.  peers_dev: device int32 [M]. */
+int netmax_sample_peers(netmax_ctx *ctx, uint64_t iter, int32_t *peers_dev);
+
+/* MLP only.  The batch D_{i,n} of Eq. (a5): B draws with replacement per worker; draw b is word b%4 of
+ * block b/4 of stream 1 mapped to floor(u n_i / 2^32).  idx_dev: device int32 [M][batch], shard-local rows.
+ * netmax_local_step makes the same draws itself; this entry point exposes them. */
+int netmax_sample_batch(netmax_ctx *ctx, uint64_t iter, int32_t *idx_dev);
+
+/* Fills g from the current parameters: the stochastic gradient of Algorithm 2's first-step update.
+ * MLP: mean cross-entropy gradient of each worker's own weights on its own batch (grouped GEMMs, one
+ * group per worker).  FLAT: g[i][j] = grad_sigma * N(0,1) by Box-Muller on block j/4 of stream 2 with
+ * u = ((word >> 9) + 0.5) 2^-23; words (0,1) give elements j, j+1 and words (2,3) give j+2, j+3.
+ * Padding columns of g are set to 0. */
+int netmax_local_step(netmax_ctx *ctx, uint64_t iter);
+
+/* Momentum apply and mix (Eq. (c0), (c1)) for all workers with the given peers (device int32 [M], each in
+ * [0, M); an index outside that range is treated as a self draw); reads x^t, g, v and the peers' rows of x^t, writes x^{t+1} and v, then swaps the roles of the two
+ * parameter buffers.  `iter` is recorded for netmax_iteration(). */
+int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev);
+
+/* Consensus distance sum_i ||x_i - mean_i x_i||^2 over the first D columns of the current parameters: the
+ * complete-graph form of the model-difference penalty of Eq. (1).  fp64 accumulation, fixed summation
+ * order.  Waits for the stream; out_host: host double. */
+int netmax_consensus_dist(netmax_ctx *ctx, double *out_host);
+
+/* Device pointer of the current parameters x^t (one of x_a, x_b), NULL if nothing is bound. */
+const float *netmax_params(const netmax_ctx *ctx);
+
+/* MLP only: device float [M], mean batch loss of each worker as computed by the last netmax_local_step. */
+const float *netmax_losses(const netmax_ctx *ctx);
+
+/* Number of netmax_mix calls so far (the next iteration's default counter). */
+uint64_t netmax_iteration(const netmax_ctx *ctx);
+
+/* Copies the tables in force to the host (any pointer may be NULL): thresholds uint32 [M][M], index of
+ * the last positive entry of each row int32 [M], mix weights float [M][M]. */
+int netmax_get_tables(netmax_ctx *ctx, uint32_t *thresholds_host, int32_t *last_host, float *w_host);
+
+/* Text of the last error of this context (ctx = NULL: of the last failed netmax_init on this thread). */
+const char *netmax_last_error(const netmax_ctx *ctx);
+
+/* Waits for the stream and frees the library's tables and scratch.  The caller's buffers are untouched. */
+int netmax_destroy(netmax_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NETMAX_H */

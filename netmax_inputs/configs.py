@@ -5,8 +5,11 @@ parameters; 32x32x3 CIFAR images; batch 128, momentum 0.9, learning rate 0.1:
 Section V-A "Datasets and models" / "Configurations") on clusters whose links
 differ in speed by 2x to 100x (Section V-A "Network").  Neither its datasets nor
 its networks are available, so every workload here is seeded and synthetic with
-those shapes and ratios.  Values the workload list leaves open (learning rates
-of cfg2..cfg5, shard size of cfg5) are frozen here.
+those shapes and ratios.  Values the workload list leaves open are frozen here:
+the learning rate of the two perceptron workloads cfg2 and cfg5 is 0.01 (the
+paper's setting for its MNIST runs, Section V-F / Appendix E), that of the flat
+workloads cfg3 and cfg4 is 0.1 (its CIFAR10 setting, Section V-A); cfg5's shards
+hold 4096 images per worker.
 """
 from __future__ import annotations
 
@@ -71,7 +74,7 @@ _WORKLOADS = {
     "cfg1": _mk("cfg1", 1, 8, "mlp", (256, 10), 0, 32, 1024, 0.05, 0.0, 0.0, "f32", 100,
                 "two_tier_10", "clusters", False),
     # M=16, MLP 784-512-10, four groups, intra/inter ratio 12
-    "cfg2": _mk("cfg2", 2, 16, "mlp", (784, 512, 10), 0, 64, 4096, 0.05, 0.9, 0.0, "f32", 1000,
+    "cfg2": _mk("cfg2", 2, 16, "mlp", (784, 512, 10), 0, 64, 4096, 0.01, 0.9, 0.0, "f32", 1000,
                 "four_group_12", "teacher_normal", False),
     # M=64, flat ResNet18-sized vector, lognormal(0,1) rack-to-rack speeds, 8 racks
     "cfg3": _mk("cfg3", 3, 64, "flat", (), 11_200_000, 0, 0, 0.1, 0.9, _SIGMA, "f32", 200,
@@ -80,7 +83,7 @@ _WORKLOADS = {
     "cfg4": _mk("cfg4", 4, 32, "flat", (), 20_000_000, 0, 0, 0.1, 0.9, _SIGMA, "f32", 200,
                 "three_tier_100_10_1", "none", False),
     # M=128, MLP 3072-1024-1024-10 on 32x32x3 images, bf16 operands, lognormal(0,1.5) links
-    "cfg5": _mk("cfg5", 5, 128, "mlp", (3072, 1024, 1024, 10), 0, 128, 4096, 0.05, 0.9, 0.0,
+    "cfg5": _mk("cfg5", 5, 128, "mlp", (3072, 1024, 1024, 10), 0, 128, 4096, 0.01, 0.9, 0.0,
                 "bf16", 500, "lognormal_1p5", "teacher_uniform", True),
 }
 

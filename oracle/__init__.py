@@ -37,6 +37,7 @@ def lib():
         L.ora_thresholds.restype = C.c_int
         L.ora_peer_of_word.restype = C.c_int32
         L.ora_grad_mlp.restype = C.c_double
+        L.ora_round_bf16.restype = C.c_double
         L.ora_consensus_dist.restype = C.c_double
         _lib = L
     return _lib
@@ -105,16 +106,23 @@ def sample_batch(M: int, B: int, shard_off: np.ndarray, seed: int, it: int) -> n
 
 
 def synth_grad(M: int, D: int, ld: int, sigma: float, seed: int, it: int,
-               out: Optional[np.ndarray] = None) -> np.ndarray:
+               out: Optional[np.ndarray] = None, col0: int = 0) -> np.ndarray:
+    """G [M, ld] = columns col0 .. col0+ld-1 of the full gradient matrix; the first D of them are valid."""
+    assert col0 % 4 == 0
     G = np.empty((M, ld), dtype=np.float32) if out is None else _chk(out, np.float32)
-    lib().ora_synth_grad(C.c_int(M), C.c_int64(D), C.c_int64(ld), C.c_double(sigma),
+    lib().ora_synth_grad(C.c_int(M), C.c_int64(D), C.c_int64(ld), C.c_int64(col0), C.c_double(sigma),
                          C.c_uint64(seed), C.c_uint64(it), _p(G))
     return G
 
 
+def round_bf16(x: float) -> float:
+    return float(lib().ora_round_bf16(C.c_double(x)))
+
+
 def grad_mlp(dims: Sequence[int], params: np.ndarray, feats: np.ndarray, labels: np.ndarray,
-             idx: np.ndarray):
-    """One worker. feats: float32 or uint16 (bfloat16 bits) [n, dims[0]]. -> (grad float32 [D], loss)."""
+             idx: np.ndarray, operands_bf16: bool = False):
+    """One worker. feats: float32 or uint16 (bfloat16 bits) [n, dims[0]]. -> (grad float32 [D], loss).
+    operands_bf16: round both operands of every matrix product to bfloat16 (the bf16 workload's arithmetic)."""
     d = np.asarray(dims, dtype=np.int64)
     nl = len(dims) - 1
     Dp = int(sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(nl)))
@@ -126,12 +134,14 @@ def grad_mlp(dims: Sequence[int], params: np.ndarray, feats: np.ndarray, labels:
     assert idx.min() >= 0 and idx.max() < feats.shape[0]
     grad = np.empty(Dp, dtype=np.float32)
     loss = lib().ora_grad_mlp(C.c_int(nl), _p(d), _p(_chk(params, np.float32)), _p(feats), C.c_int(int(bf16)),
-                              _p(_chk(labels, np.int32)), _p(idx), C.c_int(idx.shape[0]), _p(grad))
+                              C.c_int(int(operands_bf16)), _p(_chk(labels, np.int32)), _p(idx), C.c_int(idx.shape[0]),
+                              _p(grad))
     return grad, float(loss)
 
 
 def local_grad(dims: Sequence[int], X: np.ndarray, feats: np.ndarray, labels: np.ndarray,
-               shard_off: np.ndarray, idx: np.ndarray, out: Optional[np.ndarray] = None):
+               shard_off: np.ndarray, idx: np.ndarray, out: Optional[np.ndarray] = None,
+               operands_bf16: bool = False):
     """All workers. X, G: float32 [M, ld]; idx int32 [M, B] shard-local. -> (G, loss float64 [M])."""
     d = np.asarray(dims, dtype=np.int64)
     M, ld = X.shape
@@ -141,7 +151,8 @@ def local_grad(dims: Sequence[int], X: np.ndarray, feats: np.ndarray, labels: np
     G = np.empty_like(X) if out is None else _chk(out, np.float32)
     loss = np.empty(M, dtype=np.float64)
     lib().ora_local_grad(C.c_int(M), C.c_int64(ld), C.c_int(len(dims) - 1), _p(d), _p(_chk(X, np.float32)),
-                         _p(feats), C.c_int(int(bf16)), _p(_chk(labels, np.int32)), _p(_chk(shard_off, np.int64)),
+                         _p(feats), C.c_int(int(bf16)), C.c_int(int(operands_bf16)), _p(_chk(labels, np.int32)),
+                         _p(_chk(shard_off, np.int64)),
                          _p(_chk(idx, np.int32)), C.c_int(idx.shape[1]), _p(G), _p(loss))
     return G, loss
 
@@ -169,7 +180,9 @@ class Oracle:
     """State machine over the functions above: one instance = M workers of one workload."""
 
     def __init__(self, *, M, ld, D, dims, batch, lr, momentum, weight_decay, rho, grad_sigma, seed, P,
-                 adj=None, X0, feats=None, labels=None, shard_off=None):
+                 adj=None, X0, feats=None, labels=None, shard_off=None, col0=0, operands_bf16=False):
+        self.operands_bf16 = operands_bf16
+        self.col0 = col0   # flat model: the state is a window of columns of a larger problem
         self.M, self.ld, self.D, self.dims, self.batch = M, ld, D, tuple(dims), batch
         self.lr, self.mu, self.wd, self.sigma, self.seed = float(lr), float(momentum), float(weight_decay), float(grad_sigma), int(seed)
         self.adj = adj
@@ -191,10 +204,11 @@ class Oracle:
 
     def local_step(self, it):
         if len(self.dims) == 0:
-            synth_grad(self.M, self.D, self.ld, self.sigma, self.seed, it, out=self.G)
+            synth_grad(self.M, self.D, self.ld, self.sigma, self.seed, it, out=self.G, col0=self.col0)
         else:
             idx = sample_batch(self.M, self.batch, self.shard_off, self.seed, it)
-            _, self.loss = local_grad(self.dims, self.X, self.feats, self.labels, self.shard_off, idx, out=self.G)
+            _, self.loss = local_grad(self.dims, self.X, self.feats, self.labels, self.shard_off, idx, out=self.G,
+                                      operands_bf16=self.operands_bf16)
         return self.G
 
     def mix(self, peer):

@@ -168,9 +168,12 @@ void ora_sample_batch(int M, int B, const int64_t *shard_off, uint64_t seed, uin
 
 /* ------------------------------------------------------------------ synthetic gradient
  * g[i][j] = sigma * N(0,1) (stands in for a CNN's stochastic gradient, cf. the additive-noise
- * assumption of Section IV).  Block j/4 of stream 2 gives four words; u = ((word >> 8) + 0.5) 2^-24;
- * Box-Muller on (u0,u1) gives elements j, j+1 and on (u2,u3) elements j+2, j+3. Columns >= D are 0. */
-void ora_synth_grad(int M, int64_t D, int64_t ld, double sigma, uint64_t seed, uint64_t iter, float *G)
+ * assumption of Section IV).  Block j/4 of stream 2 gives four words; u = ((word >> 9) + 0.5) 2^-23,
+ * a 24-bit value strictly inside (0,1) that single precision also holds exactly;
+ * Box-Muller on (u0,u1) gives elements j, j+1 and on (u2,u3) elements j+2, j+3. Columns >= D are 0.
+ * G holds the window of columns col0 .. col0+ld-1 of the full matrix (col0 a multiple of 4; 0 = whole rows);
+ * D counts valid columns inside the window. */
+void ora_synth_grad(int M, int64_t D, int64_t ld, int64_t col0, double sigma, uint64_t seed, uint64_t iter, float *G)
 {
     const double two_pi = 6.283185307179586476925286766559;
 #pragma omp parallel for num_threads(g_threads) schedule(static)
@@ -179,10 +182,10 @@ void ora_synth_grad(int M, int64_t D, int64_t ld, double sigma, uint64_t seed, u
         for (int64_t j0 = 0; j0 < ld; j0 += 4) {
             uint32_t r[4];
             double z[4];
-            draw(seed, 2u, (uint32_t)(j0 / 4), (uint32_t)i, iter, r);
+            draw(seed, 2u, (uint32_t)((col0 + j0) / 4), (uint32_t)i, iter, r);
             for (int h = 0; h < 2; ++h) {
-                double u0 = ((double)(r[2 * h] >> 8) + 0.5) * (1.0 / 16777216.0);
-                double u1 = ((double)(r[2 * h + 1] >> 8) + 0.5) * (1.0 / 16777216.0);
+                double u0 = ((double)(r[2 * h] >> 9) + 0.5) * (1.0 / 8388608.0);
+                double u1 = ((double)(r[2 * h + 1] >> 9) + 0.5) * (1.0 / 8388608.0);
                 double rad = sqrt(-2.0 * log(u0));
                 z[2 * h] = rad * cos(two_pi * u1);
                 z[2 * h + 1] = rad * sin(two_pi * u1);
@@ -200,7 +203,14 @@ void ora_synth_grad(int M, int64_t D, int64_t ld, double sigma, uint64_t seed, u
  * W row-major [in][out], then b [out].  feats rows are float, or bfloat16 bit
  * patterns when feats_bf16 != 0; rows are indexed by idx[b] (shard-local rows of
  * `feats`, which points at the worker's shard).  Everything is accumulated in
- * double; grad is rounded to float once.  Returns the mean loss. */
+ * double; grad is rounded to float once.  Returns the mean loss.
+ *
+ * operands_bf16 != 0 selects the arithmetic that the bf16 workload prescribes
+ * ("bf16 inputs, fp32 accumulate, fp32 master weights"): both operands of every
+ * matrix product (activations, weights, back-propagated errors) are rounded to
+ * float and then to bfloat16 (nearest even) before they are multiplied; sums,
+ * biases, ReLU and softmax stay in double.  With operands_bf16 == 0 the result is
+ * the exact-arithmetic gradient. */
 static double feat_at(const void *feats, int bf16, size_t k)
 {
     if (!bf16) return (double)((const float *)feats)[k];
@@ -210,16 +220,32 @@ static double feat_at(const void *feats, int bf16, size_t k)
     return (double)f;
 }
 
-double ora_grad_mlp(int n_layers, const int64_t *dims, const float *params, const void *feats, int feats_bf16,
-                    const int32_t *labels, const int32_t *idx, int B, float *grad)
+/* value of x after rounding to float and then to bfloat16, round-to-nearest-even */
+double ora_round_bf16(double x)
 {
+    float f = (float)x;
+    uint32_t b;
+    memcpy(&b, &f, 4);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    b &= 0xFFFF0000u;
+    memcpy(&f, &b, 4);
+    return (double)f;
+}
+
+static inline double opnd(double x, int bf16) { return bf16 ? ora_round_bf16(x) : x; }
+
+double ora_grad_mlp(int n_layers, const int64_t *dims, const float *params, const void *feats, int feats_bf16,
+                    int operands_bf16, const int32_t *labels, const int32_t *idx, int B, float *grad)
+{
+    const int rb = operands_bf16;
     int64_t maxw = 0;
     for (int l = 0; l <= n_layers; ++l) if (dims[l] > maxw) maxw = dims[l];
-    /* activations a[0..n_layers] (a[0] = inputs), pre-activations share storage with a[l+1] before ReLU */
+    /* a[l] = input of layer l (a[0] = data rows, a[l] = ReLU output of layer l-1), a[n_layers] = logits */
     double **a = (double **)malloc(sizeof(double *) * (n_layers + 1));
     for (int l = 0; l <= n_layers; ++l) a[l] = (double *)malloc(sizeof(double) * B * dims[l]);
     double *dz = (double *)malloc(sizeof(double) * B * maxw);
     double *da = (double *)malloc(sizeof(double) * B * maxw);
+    double *wr = (double *)malloc(sizeof(double) * maxw);
     const int64_t d0 = dims[0];
     for (int b = 0; b < B; ++b)
         for (int64_t k = 0; k < d0; ++k)
@@ -235,12 +261,13 @@ double ora_grad_mlp(int n_layers, const int64_t *dims, const float *params, cons
         off += (size_t)(din * dout + dout);
         for (int b = 0; b < B; ++b) {
             double *z = a[l + 1] + (size_t)b * dout;
-            for (int64_t o = 0; o < dout; ++o) z[o] = (double)bias[o];
+            for (int64_t o = 0; o < dout; ++o) z[o] = 0.0;
             for (int64_t k = 0; k < din; ++k) {
-                const double x = a[l][(size_t)b * din + k];
+                const double x = opnd(a[l][(size_t)b * din + k], rb);
                 const float *Wk = W + k * dout;
-                for (int64_t o = 0; o < dout; ++o) z[o] += x * (double)Wk[o];
+                for (int64_t o = 0; o < dout; ++o) z[o] += x * opnd((double)Wk[o], rb);
             }
+            for (int64_t o = 0; o < dout; ++o) z[o] += (double)bias[o];
             if (l + 1 < n_layers)
                 for (int64_t o = 0; o < dout; ++o) z[o] = z[o] > 0.0 ? z[o] : 0.0;
         }
@@ -265,42 +292,46 @@ double ora_grad_mlp(int n_layers, const int64_t *dims, const float *params, cons
         const float *W = params + woff[l];
         float *gW = grad + woff[l], *gb = gW + din * dout;
         double *acc = (double *)calloc((size_t)dout, sizeof(double));
+        /* gW = a_l^T dz */
         for (int64_t k = 0; k < din; ++k) {
             memset(acc, 0, sizeof(double) * dout);
             for (int b = 0; b < B; ++b) {
-                const double x = a[l][(size_t)b * din + k];
+                const double x = opnd(a[l][(size_t)b * din + k], rb);
                 const double *d = dz + (size_t)b * dout;
-                for (int64_t o = 0; o < dout; ++o) acc[o] += x * d[o];
+                for (int64_t o = 0; o < dout; ++o) acc[o] += x * opnd(d[o], rb);
             }
             for (int64_t o = 0; o < dout; ++o) gW[k * dout + o] = (float)acc[o];
         }
+        /* gb = column sums of dz (no product: not rounded) */
         memset(acc, 0, sizeof(double) * dout);
         for (int b = 0; b < B; ++b)
             for (int64_t o = 0; o < dout; ++o) acc[o] += dz[(size_t)b * dout + o];
         for (int64_t o = 0; o < dout; ++o) gb[o] = (float)acc[o];
         free(acc);
         if (l > 0) {
-            for (int b = 0; b < B; ++b)
+            /* da = dz W^T, then through the ReLU: derivative 1 where the activation is positive, else 0 */
+            for (int b = 0; b < B; ++b) {
+                const double *d = dz + (size_t)b * dout;
+                for (int64_t o = 0; o < dout; ++o) wr[o] = opnd(d[o], rb);
                 for (int64_t k = 0; k < din; ++k) {
                     const float *Wk = W + k * dout;
-                    const double *d = dz + (size_t)b * dout;
                     double s = 0.0;
-                    for (int64_t o = 0; o < dout; ++o) s += d[o] * (double)Wk[o];
-                    /* ReLU derivative: 1 where the hidden activation is positive, else 0 */
+                    for (int64_t o = 0; o < dout; ++o) s += wr[o] * opnd((double)Wk[o], rb);
                     da[(size_t)b * din + k] = a[l][(size_t)b * din + k] > 0.0 ? s : 0.0;
                 }
+            }
             double *t = dz; dz = da; da = t;
         }
     }
     for (int l = 0; l <= n_layers; ++l) free(a[l]);
-    free(a); free(dz); free(da); free(woff);
+    free(a); free(dz); free(da); free(wr); free(woff);
     return loss;
 }
 
 /* All workers: gradient of worker i from row i of X into row i of G (padding columns set to 0).
  * feats/labels hold all shards; shard_off[M+1] delimits them; idx is [M][B]. loss (may be NULL) is [M]. */
 void ora_local_grad(int M, int64_t ld, int n_layers, const int64_t *dims, const float *X, const void *feats,
-                    int feats_bf16, const int32_t *labels, const int64_t *shard_off, const int32_t *idx, int B,
+                    int feats_bf16, int operands_bf16, const int32_t *labels, const int64_t *shard_off, const int32_t *idx, int B,
                     float *G, double *loss)
 {
     int64_t D = 0;
@@ -309,7 +340,7 @@ void ora_local_grad(int M, int64_t ld, int n_layers, const int64_t *dims, const 
 #pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
     for (int i = 0; i < M; ++i) {
         const char *f = (const char *)feats + (size_t)shard_off[i] * dims[0] * esz;
-        double L = ora_grad_mlp(n_layers, dims, X + (size_t)i * ld, f, feats_bf16, labels + shard_off[i],
+        double L = ora_grad_mlp(n_layers, dims, X + (size_t)i * ld, f, feats_bf16, operands_bf16, labels + shard_off[i],
                                 idx + (size_t)i * B, B, G + (size_t)i * ld);
         for (int64_t j = D; j < ld; ++j) G[(size_t)i * ld + j] = 0.0f;
         if (loss) loss[i] = L;

@@ -1,0 +1,304 @@
+"""ctypes binding of libnetmax.so: the same entry points as include/netmax.h, argument
+marshalling only.  Device memory comes from PyTorch tensors (their data_ptr()); every step of
+the iteration runs in the library's HIP kernels.  There is no CPU fallback: a missing library or
+a failing call raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libnetmax.so")
+
+NETMAX_MAX_LAYERS = 7
+NETMAX_OK, NETMAX_EINVAL, NETMAX_EINFEASIBLE, NETMAX_ESTATE, NETMAX_EDEVICE, NETMAX_ENOMEM = range(6)
+NETMAX_FLAT, NETMAX_MLP = 0, 1
+NETMAX_F32, NETMAX_BF16 = 0, 1
+
+EXPORTS = (
+    "netmax_init", "netmax_build_tables", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
+    "netmax_bind_data", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix",
+    "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
+    "netmax_last_error", "netmax_destroy",
+)
+
+
+class NetmaxError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"netmax status {code}: {text}")
+        self.code = code
+
+
+class netmax_config(C.Structure):
+    _fields_ = [
+        ("M", C.c_int32), ("D", C.c_int64), ("ld", C.c_int64),
+        ("model", C.c_int32), ("n_layers", C.c_int32), ("dims", C.c_int64 * (NETMAX_MAX_LAYERS + 1)),
+        ("batch", C.c_int32), ("gemm_in", C.c_int32),
+        ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float), ("rho", C.c_float),
+        ("grad_sigma", C.c_float),
+        ("seed", C.c_uint64), ("strict_o3", C.c_int32),
+        ("P", C.c_void_p), ("adj", C.c_void_p), ("stream", C.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def load():
+    """Loads the built library (building it first only if it is absent)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build
+        build()
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
+    sig = {
+        "netmax_init": (C.c_int, [C.POINTER(vp), C.POINTER(netmax_config)]),
+        "netmax_build_tables": (C.c_int, [i32, vp, vp, f32, f32, i32, vp, vp, vp]),
+        "netmax_set_policy": (C.c_int, [vp, vp, f32]),
+        "netmax_set_lr": (C.c_int, [vp, f32]),
+        "netmax_bind_state": (C.c_int, [vp, vp, vp, vp, vp]),
+        "netmax_bind_data": (C.c_int, [vp, vp, vp, vp]),
+        "netmax_sample_peers": (C.c_int, [vp, u64, vp]),
+        "netmax_sample_batch": (C.c_int, [vp, u64, vp]),
+        "netmax_local_step": (C.c_int, [vp, u64]),
+        "netmax_mix": (C.c_int, [vp, u64, vp]),
+        "netmax_consensus_dist": (C.c_int, [vp, C.POINTER(C.c_double)]),
+        "netmax_params": (vp, [vp]),
+        "netmax_losses": (vp, [vp]),
+        "netmax_iteration": (u64, [vp]),
+        "netmax_get_tables": (C.c_int, [vp, vp, vp, vp]),
+        "netmax_last_error": (C.c_char_p, [vp]),
+        "netmax_destroy": (C.c_int, [vp]),
+    }
+    for name, (res, args) in sig.items():
+        f = getattr(L, name)
+        f.restype, f.argtypes = res, args
+    _lib = L
+    return L
+
+
+def _err(ctx) -> str:
+    t = load().netmax_last_error(ctx)
+    return t.decode() if t else ""
+
+
+def _check(rc: int, ctx=None):
+    if rc != NETMAX_OK:
+        raise NetmaxError(rc, _err(ctx))
+
+
+def _host(a: Optional[np.ndarray], dtype) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _dp(t, dtype=None):
+    """Device pointer of a contiguous CUDA/HIP torch tensor."""
+    import torch
+    assert isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous(), "need a contiguous device tensor"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+# ---- the C entry points, one Python function each -------------------------------------------------
+
+def netmax_build_tables(P: np.ndarray, adj: Optional[np.ndarray], lr: float, rho: float, strict_o3: bool = False):
+    P = _host(P, np.float64)
+    M = P.shape[0]
+    adj = _host(adj, np.uint8)
+    thr = np.empty((M, M), np.uint32)
+    last = np.empty(M, np.int32)
+    w = np.empty((M, M), np.float32)
+    _check(load().netmax_build_tables(M, _hp(P), _hp(adj), lr, rho, int(strict_o3), _hp(thr), _hp(last), _hp(w)))
+    return thr, last, w
+
+
+def netmax_init(*, M: int, D: int, ld: int, model: int, dims: Sequence[int] = (), batch: int = 0,
+                gemm_in: int = NETMAX_F32, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
+                rho: float, grad_sigma: float = 0.0, seed: int, strict_o3: bool = False, P: np.ndarray,
+                adj: Optional[np.ndarray] = None, stream: int = 0):
+    cfg = netmax_config()
+    cfg.M, cfg.D, cfg.ld, cfg.model = M, D, ld, model
+    cfg.n_layers = max(len(dims) - 1, 0)
+    for k, d in enumerate(dims):
+        cfg.dims[k] = d
+    cfg.batch, cfg.gemm_in = batch, gemm_in
+    cfg.lr, cfg.momentum, cfg.weight_decay, cfg.rho, cfg.grad_sigma = lr, momentum, weight_decay, rho, grad_sigma
+    cfg.seed, cfg.strict_o3 = seed, int(strict_o3)
+    P = _host(P, np.float64)
+    assert P.shape == (M, M)
+    adj = _host(adj, np.uint8)
+    cfg.P, cfg.adj = P.ctypes.data, (adj.ctypes.data if adj is not None else None)
+    cfg.stream = stream
+    ctx = C.c_void_p()
+    _check(load().netmax_init(C.byref(ctx), C.byref(cfg)))
+    return ctx
+
+
+def netmax_set_policy(ctx, P: np.ndarray, rho: float):
+    P = _host(P, np.float64)
+    _check(load().netmax_set_policy(ctx, _hp(P), rho), ctx)
+
+
+def netmax_set_lr(ctx, lr: float):
+    _check(load().netmax_set_lr(ctx, lr), ctx)
+
+
+def netmax_bind_state(ctx, x_a, x_b, v, g):
+    import torch
+    _check(load().netmax_bind_state(ctx, _dp(x_a, torch.float32), _dp(x_b, torch.float32), _dp(v, torch.float32),
+                                    _dp(g, torch.float32)), ctx)
+
+
+def netmax_bind_data(ctx, feats, labels, shard_off: np.ndarray):
+    import torch
+    so = _host(shard_off, np.int64)
+    _check(load().netmax_bind_data(ctx, _dp(feats), _dp(labels, torch.int32), _hp(so)), ctx)
+
+
+def netmax_sample_peers(ctx, it: int, peers):
+    import torch
+    _check(load().netmax_sample_peers(ctx, it, _dp(peers, torch.int32)), ctx)
+
+
+def netmax_sample_batch(ctx, it: int, idx):
+    import torch
+    _check(load().netmax_sample_batch(ctx, it, _dp(idx, torch.int32)), ctx)
+
+
+def netmax_local_step(ctx, it: int):
+    _check(load().netmax_local_step(ctx, it), ctx)
+
+
+def netmax_mix(ctx, it: int, peers):
+    import torch
+    _check(load().netmax_mix(ctx, it, _dp(peers, torch.int32)), ctx)
+
+
+def netmax_consensus_dist(ctx) -> float:
+    out = C.c_double()
+    _check(load().netmax_consensus_dist(ctx, C.byref(out)), ctx)
+    return out.value
+
+
+def netmax_params(ctx) -> int:
+    return load().netmax_params(ctx) or 0
+
+
+def netmax_losses(ctx) -> int:
+    return load().netmax_losses(ctx) or 0
+
+
+def netmax_iteration(ctx) -> int:
+    return int(load().netmax_iteration(ctx))
+
+
+def netmax_get_tables(ctx, M: int):
+    thr = np.empty((M, M), np.uint32)
+    last = np.empty(M, np.int32)
+    w = np.empty((M, M), np.float32)
+    _check(load().netmax_get_tables(ctx, _hp(thr), _hp(last), _hp(w)), ctx)
+    return thr, last, w
+
+
+def netmax_destroy(ctx):
+    _check(load().netmax_destroy(ctx))
+
+
+# ---- a holder for the device buffers of one run ---------------------------------------------------
+
+class NetMax:
+    """Owns the torch tensors (device memory) of one run and forwards every step to the library."""
+
+    def __init__(self, *, M, D, ld, model, dims=(), batch=0, gemm_in=NETMAX_F32, lr, momentum=0.0,
+                 weight_decay=0.0, rho, grad_sigma=0.0, seed, P, adj=None, strict_o3=False,
+                 X0: Optional[np.ndarray] = None, feats=None, labels=None, shard_off=None, device="cuda:0"):
+        import torch
+        self.M, self.D, self.ld, self.batch = M, D, ld, batch
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.stream = torch.cuda.current_stream(self.device).cuda_stream
+        self.ctx = netmax_init(M=M, D=D, ld=ld, model=model, dims=dims, batch=batch, gemm_in=gemm_in, lr=lr,
+                               momentum=momentum, weight_decay=weight_decay, rho=rho, grad_sigma=grad_sigma,
+                               seed=seed, strict_o3=strict_o3, P=P, adj=adj, stream=self.stream)
+        kw = dict(dtype=torch.float32, device=self.device)
+        self.x_a = torch.empty((M, ld), **kw)
+        self.x_b = torch.empty((M, ld), **kw)
+        self.v = torch.zeros((M, ld), **kw)
+        self.g = torch.zeros((M, ld), **kw)
+        if X0 is not None:
+            self.x_a.copy_(torch.from_numpy(np.ascontiguousarray(X0, dtype=np.float32)))
+        else:
+            self.x_a.zero_()
+        self.x_b.zero_()
+        self.peers = torch.zeros(M, dtype=torch.int32, device=self.device)
+        netmax_bind_state(self.ctx, self.x_a, self.x_b, self.v, self.g)
+        self.feats = self.labels = None
+        if feats is not None:
+            if isinstance(feats, np.ndarray):
+                if feats.dtype == np.uint16:   # bfloat16 bit patterns
+                    feats = torch.from_numpy(feats.view(np.int16)).to(self.device).view(torch.bfloat16)
+                else:
+                    feats = torch.from_numpy(feats).to(self.device)
+            if isinstance(labels, np.ndarray):
+                labels = torch.from_numpy(labels).to(self.device)
+            self.feats, self.labels = feats.contiguous(), labels.contiguous()
+            netmax_bind_data(self.ctx, self.feats, self.labels, shard_off)
+
+    def sample_peers(self, it: int):
+        netmax_sample_peers(self.ctx, it, self.peers)
+        return self.peers
+
+    def local_step(self, it: int):
+        netmax_local_step(self.ctx, it)
+
+    def mix(self, it: int, peers=None):
+        netmax_mix(self.ctx, it, self.peers if peers is None else peers)
+
+    def step(self, it: int):
+        netmax_sample_peers(self.ctx, it, self.peers)
+        netmax_local_step(self.ctx, it)
+        netmax_mix(self.ctx, it, self.peers)
+
+    def consensus_dist(self) -> float:
+        return netmax_consensus_dist(self.ctx)
+
+    def params(self):
+        """The tensor that currently holds x^t."""
+        p = netmax_params(self.ctx)
+        return self.x_a if p == self.x_a.data_ptr() else self.x_b
+
+    def losses(self):
+        import torch
+        p = netmax_losses(self.ctx)
+        if not p:
+            return None
+        out = torch.empty(self.M, dtype=torch.float32, device=self.device)
+        # device-to-device copy of the library's buffer through HIP's runtime
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        torch.cuda.current_stream(self.device).synchronize()
+        rc = hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(p), C.c_size_t(4 * self.M), C.c_int(3))
+        assert rc == 0
+        return out
+
+    def close(self):
+        if self.ctx is not None:
+            netmax_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

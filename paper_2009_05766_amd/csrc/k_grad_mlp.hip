@@ -1,0 +1,261 @@
+// Per-worker gradient of a ReLU perceptron with softmax cross-entropy (one layer = softmax regression):
+// the stochastic gradient of Algorithm 2's first-step update, for all workers at once.  Every GEMM is
+// grouped, one group per worker, because each worker multiplies its own batch with its own weights.
+//
+// This file holds the general tiled kernels (any shape, fp32 FMA).  With bf16 operands the inputs of
+// every product are rounded to bfloat16 first and accumulated in fp32.
+#include "kernels.h"
+
+namespace netmax {
+
+constexpr int TM = 64, TN = 64, TK = 16, GEMM_THREADS = 256;
+
+__device__ __forceinline__ float round_bf16(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    b += 0x7FFFu + ((b >> 16) & 1u);     // nearest even
+    return __uint_as_float(b & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// Input of layer l for worker g, batch row r, feature k: the gathered data row for l = 0, else the
+// previous layer's activation.
+struct LayerInput {
+    const void *feats; int feats_bf16; const int64_t *row0; const int32_t *idx; const float *act_prev;
+    int B; int64_t din; int first; int round;
+    __device__ __forceinline__ float at(int g, int r, int64_t k) const
+    {
+        if (first) {
+            const int64_t row = row0[g] + idx[(size_t)g * B + r];
+            return feats_bf16 ? bf16_bits_to_float(((const uint16_t *)feats)[row * din + k])
+                              : (round ? round_bf16(((const float *)feats)[row * din + k])
+                                       : ((const float *)feats)[row * din + k]);
+        }
+        const float a = act_prev[((size_t)g * B + r) * din + k];
+        return round ? round_bf16(a) : a;
+    }
+};
+
+// Z = A W + b, optional ReLU.  rows = batch, cols = dout, K = din.
+struct FwdProblem {
+    static constexpr bool A_K_FAST = true, B_C_FAST = true;
+    LayerInput in; const float *X; int64_t ld, woff, din, dout; int B, relu, round; float *out;
+    __device__ int rows() const { return B; }
+    __device__ int64_t cols() const { return dout; }
+    __device__ int64_t depth() const { return din; }
+    __device__ float a(int g, int64_t r, int64_t k) const { return in.at(g, (int)r, k); }
+    __device__ float b(int g, int64_t k, int64_t c) const
+    {
+        const float w = X[(size_t)g * ld + woff + k * dout + c];
+        return round ? round_bf16(w) : w;
+    }
+    __device__ void store(int g, int64_t r, int64_t c, float acc) const
+    {
+        float z = acc + X[(size_t)g * ld + woff + din * dout + c];
+        if (relu) z = z > 0.0f ? z : 0.0f;
+        out[((size_t)g * B + r) * dout + c] = z;
+    }
+};
+
+// dA = (dZ W^T) * [A > 0].  rows = batch, cols = din, K = dout.
+struct DgradProblem {
+    static constexpr bool A_K_FAST = true, B_C_FAST = false;
+    const float *dz; const float *X; const float *act; int64_t ld, woff, din, dout; int B, round; float *out;
+    __device__ int rows() const { return B; }
+    __device__ int64_t cols() const { return din; }
+    __device__ int64_t depth() const { return dout; }
+    __device__ float a(int g, int64_t r, int64_t k) const
+    {
+        const float d = dz[((size_t)g * B + r) * dout + k];
+        return round ? round_bf16(d) : d;
+    }
+    __device__ float b(int g, int64_t k, int64_t c) const
+    {
+        const float w = X[(size_t)g * ld + woff + c * dout + k];
+        return round ? round_bf16(w) : w;
+    }
+    __device__ void store(int g, int64_t r, int64_t c, float acc) const
+    {
+        const size_t q = ((size_t)g * B + r) * din + c;
+        out[q] = act[q] > 0.0f ? acc : 0.0f;
+    }
+};
+
+// dW = A^T dZ.  rows = din, cols = dout, K = batch.
+struct WgradProblem {
+    static constexpr bool A_K_FAST = false, B_C_FAST = true;
+    LayerInput in; const float *dz; int64_t ld, woff, din, dout; int B, round; float *G;
+    __device__ int64_t rows() const { return din; }
+    __device__ int64_t cols() const { return dout; }
+    __device__ int64_t depth() const { return B; }
+    __device__ float a(int g, int64_t r, int64_t k) const { return in.at(g, (int)k, r); }
+    __device__ float b(int g, int64_t k, int64_t c) const
+    {
+        const float d = dz[((size_t)g * B + k) * dout + c];
+        return round ? round_bf16(d) : d;
+    }
+    __device__ void store(int g, int64_t r, int64_t c, float acc) const
+    {
+        G[(size_t)g * ld + woff + r * dout + c] = acc;
+    }
+};
+
+// 64 x 64 output tile per workgroup, 4 x 4 per thread, K in steps of 16 through LDS.
+template <class Problem>
+__global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
+{
+    __shared__ float As[TK][TM + 4];
+    __shared__ float Bs[TK][TN + 4];
+    const int g = blockIdx.z, tid = threadIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.y * TM, col0 = (int64_t)blockIdx.x * TN;
+    const int64_t R = p.rows(), C = p.cols(), K = p.depth();
+    const int ty = tid / 16, tx = tid % 16;
+    float acc[4][4] = {};
+    for (int64_t k0 = 0; k0 < K; k0 += TK) {
+#pragma unroll
+        for (int q = 0; q < (TM * TK) / GEMM_THREADS; ++q) {
+            const int e = tid + q * GEMM_THREADS;
+            int kk, r;
+            if (Problem::A_K_FAST) { kk = e % TK; r = e / TK; } else { r = e % TM; kk = e / TM; }
+            As[kk][r] = (row0 + r < R && k0 + kk < K) ? p.a(g, row0 + r, k0 + kk) : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < (TN * TK) / GEMM_THREADS; ++q) {
+            const int e = tid + q * GEMM_THREADS;
+            int kk, c;
+            if (Problem::B_C_FAST) { c = e % TN; kk = e / TN; } else { kk = e % TK; c = e / TK; }
+            Bs[kk][c] = (col0 + c < C && k0 + kk < K) ? p.b(g, k0 + kk, col0 + c) : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < TK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { a[e] = As[kk][ty * 4 + e]; b[e] = Bs[kk][tx * 4 + e]; }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(a[r], b[c], acc[r][c]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int64_t rr = row0 + ty * 4 + r, cc = col0 + tx * 4 + c;
+            if (rr < R && cc < C) p.store(g, rr, cc, acc[r][c]);
+        }
+}
+
+template <class Problem>
+static void launch_gemm(hipStream_t s, const Problem &p, int groups, int64_t rows, int64_t cols)
+{
+    dim3 grid((unsigned)((cols + TN - 1) / TN), (unsigned)((rows + TM - 1) / TM), (unsigned)groups);
+    hipLaunchKernelGGL(grouped_gemm_kernel<Problem>, grid, dim3(GEMM_THREADS), 0, s, p);
+}
+
+// Softmax cross-entropy on the logits: dz = (softmax - onehot) / B and the mean loss per worker.
+// One workgroup per worker, one thread per batch row.
+__global__ void __launch_bounds__(1024)
+softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const int32_t *__restrict__ labels,
+                    const int64_t *__restrict__ row0, const int32_t *__restrict__ idx, float *__restrict__ dz,
+                    float *__restrict__ loss)
+{
+    __shared__ float red[1024];
+    const int g = blockIdx.x, b = threadIdx.x;
+    float l = 0.0f;
+    if (b < B) {
+        const float *z = logits + ((size_t)g * B + b) * C;
+        float *d = dz + ((size_t)g * B + b) * C;
+        float mx = z[0];
+        for (int64_t o = 1; o < C; ++o) mx = fmaxf(mx, z[o]);
+        float sum = 0.0f;
+        for (int64_t o = 0; o < C; ++o) sum += expf(z[o] - mx);
+        const int y = labels[row0[g] + idx[(size_t)g * B + b]];
+        l = logf(sum) - (z[y] - mx);
+        const float inv = 1.0f / sum, invB = 1.0f / (float)B;
+        for (int64_t o = 0; o < C; ++o) d[o] = (expf(z[o] - mx) * inv - (o == y ? 1.0f : 0.0f)) * invB;
+    }
+    red[b] = l;
+    __syncthreads();
+    for (int stride = 512; stride > 0; stride >>= 1) {
+        if (b < stride && b + stride < (int)blockDim.x) red[b] += red[b + stride];
+        __syncthreads();
+    }
+    if (b == 0) loss[g] = red[0] / (float)B;
+}
+
+// db = column sums of dZ; thread per (worker, output).  With zero_from >= 0 the threads also clear the
+// padding columns zero_from..ld-1 of the gradient row.
+__global__ void __launch_bounds__(256)
+bias_grad_kernel(int M, int B, int64_t dout, const float *__restrict__ dz, int64_t ld, int64_t boff,
+                 float *__restrict__ G)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)M * dout) return;
+    const int g = (int)(t / dout);
+    const int64_t c = t - (int64_t)g * dout;
+    float s = 0.0f;
+    for (int b = 0; b < B; ++b) s += dz[((size_t)g * B + b) * dout + c];
+    G[(size_t)g * ld + boff + c] = s;
+}
+
+__global__ void __launch_bounds__(256) zero_padding_kernel(int M, int64_t D, int64_t ld, float *__restrict__ G)
+{
+    const int64_t pad = ld - D;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)M * pad) return;
+    const int g = (int)(t / pad);
+    G[(size_t)g * ld + D + (t - (int64_t)g * pad)] = 0.0f;
+}
+
+void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
+{
+    const int L = p.n_layers;
+    auto input_of = [&](int l) {
+        LayerInput in;
+        in.feats = p.feats; in.feats_bf16 = p.bf16; in.row0 = p.row0; in.idx = p.idx;
+        in.act_prev = l > 0 ? p.act[l] : nullptr;
+        in.B = p.B; in.din = p.dims[l]; in.first = (l == 0); in.round = p.bf16;
+        return in;
+    };
+    // forward
+    for (int l = 0; l < L; ++l) {
+        FwdProblem f;
+        f.in = input_of(l); f.X = X; f.ld = p.ld; f.woff = p.woff[l]; f.din = p.dims[l]; f.dout = p.dims[l + 1];
+        f.B = p.B; f.relu = (l + 1 < L); f.round = p.bf16; f.out = p.act[l + 1];
+        launch_gemm(s, f, p.M, p.B, f.dout);
+    }
+    // loss and dZ of the last layer
+    const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3(p.M), dim3(sm_threads), 0, s, p.B, p.dims[L], p.act[L], p.labels,
+                       p.row0, p.idx, p.dz[0], p.loss);
+    // backward
+    int cur = 0;
+    for (int l = L - 1; l >= 0; --l) {
+        const int64_t din = p.dims[l], dout = p.dims[l + 1];
+        WgradProblem wg;
+        wg.in = input_of(l); wg.dz = p.dz[cur]; wg.ld = p.ld; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
+        wg.B = p.B; wg.round = p.bf16; wg.G = G;
+        launch_gemm(s, wg, p.M, din, dout);
+        const int64_t nb = (int64_t)p.M * dout;
+        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, p.M, p.B, dout,
+                           p.dz[cur], p.ld, p.woff[l] + din * dout, G);
+        if (l > 0) {
+            DgradProblem dg;
+            dg.dz = p.dz[cur]; dg.X = X; dg.act = p.act[l]; dg.ld = p.ld; dg.woff = p.woff[l]; dg.din = din;
+            dg.dout = dout; dg.B = p.B; dg.round = p.bf16; dg.out = p.dz[cur ^ 1];
+            launch_gemm(s, dg, p.M, p.B, din);
+            cur ^= 1;
+        }
+    }
+    int64_t D = p.woff[L - 1] + p.dims[L - 1] * p.dims[L] + p.dims[L];
+    if (p.ld > D) {
+        const int64_t n = (int64_t)p.M * (p.ld - D);
+        hipLaunchKernelGGL(zero_padding_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.M, D, p.ld, G);
+    }
+}
+
+}  // namespace netmax

@@ -1,0 +1,58 @@
+// Peer selection (Algorithm 2: "select a neighbor m with probability p_im") and batch draws
+// (the sampled dataset D_{i,n} of Eq. (a5)).  Integer work only; results are reproducible bit for bit.
+#include "kernels.h"
+#include "philox.h"
+
+namespace netmax {
+
+// One thread per worker.  Row i of `thr` holds non-decreasing cumulative thresholds; the peer is the
+// number of thresholds <= u (the first m whose threshold exceeds u), clamped to the last positive entry.
+__global__ void __launch_bounds__(256) sample_peers_kernel(int M, const uint32_t *__restrict__ thr,
+                                                           const int32_t *__restrict__ last, uint64_t seed,
+                                                           uint64_t iter, int32_t *__restrict__ peer)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    const uint32_t u = draw_block(seed, STREAM_PEER, 0u, (uint32_t)i, iter).a;
+    const uint32_t *row = thr + (size_t)i * M;
+    int lo = 0, hi = M;  // upper bound: first position with row[pos] > u
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (row[mid] <= u) lo = mid + 1; else hi = mid;
+    }
+    const int l = last[i];
+    peer[i] = lo < l ? lo : l;
+}
+
+// One thread per Philox block of four draws: idx[i][4q..4q+3] = floor(word * n_i / 2^32).
+__global__ void __launch_bounds__(256) sample_batch_kernel(int M, int B, const int32_t *__restrict__ n_rows,
+                                                           uint64_t seed, uint64_t iter, int32_t *__restrict__ idx)
+{
+    const int quads = (B + 3) >> 2;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= M * quads) return;
+    const int i = t / quads, q = t - i * quads;
+    const Words4 r = draw_block(seed, STREAM_BATCH, (uint32_t)q, (uint32_t)i, iter);
+    const uint32_t n = (uint32_t)n_rows[i];
+    const uint32_t w[4] = {r.a, r.b, r.c, r.d};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int b = 4 * q + e;
+        if (b < B) idx[(size_t)i * B + b] = (int32_t)__umulhi(w[e], n);
+    }
+}
+
+void launch_sample_peers(hipStream_t s, int M, const uint32_t *thr, const int32_t *last, uint64_t seed,
+                         uint64_t iter, int32_t *peer)
+{
+    hipLaunchKernelGGL(sample_peers_kernel, dim3((M + 255) / 256), dim3(256), 0, s, M, thr, last, seed, iter, peer);
+}
+
+void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uint64_t seed, uint64_t iter,
+                         int32_t *idx)
+{
+    const int n = M * ((B + 3) / 4);
+    hipLaunchKernelGGL(sample_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, s, M, B, n_rows, seed, iter, idx);
+}
+
+}  // namespace netmax

@@ -1,0 +1,47 @@
+// Internal launch interface between the C ABI (netmax_api.hip) and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace netmax {
+
+// Peer selection of Algorithm 2: one Philox draw per worker against fixed-point cumulative thresholds.
+void launch_sample_peers(hipStream_t s, int M, const uint32_t *thr, const int32_t *last, uint64_t seed,
+                         uint64_t iter, int32_t *peer);
+
+// Batch draws (with replacement) for every worker; n_rows[i] = shard size of worker i.
+void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uint64_t seed, uint64_t iter,
+                         int32_t *idx);
+
+// g[i][j] = sigma * N(0,1) from Philox + Box-Muller; padding columns are zeroed.
+void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, uint64_t iter,
+                       float *G);
+
+// Momentum apply + mix, Eq. (c0)/(c1), for all workers.
+void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float *G, float *V, float *Xnext,
+                const int32_t *peer, const float *w, float alpha, float mu, float wd);
+
+// Consensus distance: per-block partial sums (double), then a fixed-order final sum into out_dev[0].
+// partial must hold consensus_partials(ld) doubles.
+int consensus_partials(int64_t ld);
+void launch_consensus(hipStream_t s, int M, int64_t D, int64_t ld, const float *X, double *partial,
+                      double *out_dev);
+
+// Per-worker MLP / softmax-regression gradient (grouped GEMMs).
+struct MlpPlan {
+    int M, n_layers, B;
+    int64_t dims[8];
+    int64_t woff[8];        // offset of layer l's W inside a parameter row; the bias follows the matrix
+    int64_t ld;
+    int bf16;               // operands rounded to bfloat16 (features are stored as bfloat16)
+    const void *feats;      // [n_total][dims[0]]
+    const int32_t *labels;  // [n_total]
+    const int64_t *row0;    // device [M]: first feature row of each worker's shard
+    const int32_t *idx;     // device [M][B] shard-local batch rows
+    float *act[8];          // act[l], l = 1..n_layers: [M][B][dims[l]] post-activation (logits for the last)
+    float *dz[2];           // two ping-pong buffers [M][B][max width]
+    float *loss;            // [M]
+};
+void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G);
+
+}  // namespace netmax

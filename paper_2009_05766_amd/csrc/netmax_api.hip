@@ -1,0 +1,474 @@
+// C ABI of the library (see include/netmax.h): context, host-side policy tables, argument checks and
+// kernel launches.  Everything that touches model data runs in the kernels of this directory.
+#include "../../include/netmax.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace netmax;
+
+struct netmax_ctx {
+    netmax_config cfg{};
+    std::vector<double> P;
+    std::vector<uint8_t> adj;
+    bool has_adj = false;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    // policy tables (device) and their host images
+    uint32_t *d_thr = nullptr;
+    int32_t *d_last = nullptr;
+    float *d_w = nullptr;
+    std::vector<uint32_t> h_thr;
+    std::vector<int32_t> h_last;
+    std::vector<float> h_w;
+    // caller-owned state
+    float *x_cur = nullptr, *x_next = nullptr, *v = nullptr, *g = nullptr;
+    // caller-owned data and the library's scratch for the perceptron gradient
+    const void *feats = nullptr;
+    const int32_t *labels = nullptr;
+    bool data_bound = false;
+    int64_t *d_row0 = nullptr;
+    int32_t *d_nrows = nullptr;
+    int32_t *d_idx = nullptr;
+    float *d_act[NETMAX_MAX_LAYERS + 1] = {};
+    float *d_dz[2] = {};
+    float *d_loss = nullptr;
+    int32_t *d_flag = nullptr;
+    int64_t woff[NETMAX_MAX_LAYERS + 1] = {};
+    // consensus distance
+    double *d_partial = nullptr, *d_cd = nullptr;
+    uint64_t iterations = 0;
+    std::string err;
+};
+
+static thread_local std::string g_init_error;
+
+static int fail(netmax_ctx *ctx, int code, const std::string &msg)
+{
+    if (ctx) ctx->err = msg; else g_init_error = msg;
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                         \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? NETMAX_ENOMEM : NETMAX_EDEVICE,           \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));                        \
+    } while (0)
+
+// --------------------------------------------------------------------------------------------------
+// Policy tables.  Row i of P becomes cumulative thresholds in 32-bit fixed point: the running sum of
+// the row, scaled by 2^32 and rounded to nearest, with every position from the last positive entry on
+// forced to 2^32 (stored as 2^32 - 1 together with `last`, which the sampler clamps to).  Entries of
+// probability zero repeat the previous threshold and can never be drawn.
+// The second-step weight is w_im = alpha rho (d_im + d_mi) / (2 p_im) (Algorithm 2), 0 for m = i.
+static int build_tables(int M, const double *P, const uint8_t *adj, double alpha, double rho, bool strict,
+                        std::vector<uint32_t> &thr, std::vector<int32_t> &last, std::vector<float> &w,
+                        std::string &why)
+{
+    thr.assign((size_t)M * M, 0u);
+    last.assign(M, 0);
+    w.assign((size_t)M * M, 0.0f);
+    const double limit = strict ? 0.5 : 1.0;
+    char buf[200];
+    for (int i = 0; i < M; ++i) {
+        const double *row = P + (size_t)i * M;
+        double total = 0.0;
+        int tail = -1;
+        for (int m = 0; m < M; ++m) {
+            const double p = row[m];
+            if (!(p >= 0.0) || !std::isfinite(p)) {
+                snprintf(buf, sizeof buf, "P[%d][%d] = %g is not a probability", i, m, p);
+                why = buf;
+                return NETMAX_EINVAL;
+            }
+            if (p > 0.0) {
+                tail = m;
+                if (adj && m != i && !adj[(size_t)i * M + m]) {
+                    snprintf(buf, sizeof buf, "P[%d][%d] > 0 but the workers are not neighbours (constraint (o4))", i, m);
+                    why = buf;
+                    return NETMAX_EINVAL;
+                }
+            }
+            total += p;
+        }
+        if (tail < 0 || std::fabs(total - 1.0) > 1e-9) {
+            snprintf(buf, sizeof buf, "row %d of P sums to %.12g, expected 1", i, total);
+            why = buf;
+            return NETMAX_EINVAL;
+        }
+        last[i] = tail;
+        double running = 0.0;
+        for (int m = 0; m < M; ++m) {
+            running += row[m];
+            uint64_t fixed;
+            if (m >= tail) {
+                fixed = 1ull << 32;
+            } else {
+                const double scaled = std::floor(std::ldexp(running, 32) + 0.5);
+                fixed = scaled >= 4294967296.0 ? (1ull << 32) : (uint64_t)scaled;
+            }
+            thr[(size_t)i * M + m] = fixed > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)fixed;
+            if (m != i && row[m] > 0.0) {
+                const double links = adj ? (double)((adj[(size_t)i * M + m] != 0) + (adj[(size_t)m * M + i] != 0)) : 2.0;
+                const double weight = alpha * rho * links / (2.0 * row[m]);
+                if (!(weight < limit)) {
+                    snprintf(buf, sizeof buf, "mix weight of pair (%d,%d) is %g, must be below %g%s", i, m, weight, limit,
+                             strict ? " (constraint (o3))" : "");
+                    why = buf;
+                    return NETMAX_EINFEASIBLE;
+                }
+                w[(size_t)i * M + m] = (float)weight;
+            }
+        }
+    }
+    return NETMAX_OK;
+}
+
+static int upload_tables(netmax_ctx *ctx)
+{
+    const size_t mm = (size_t)ctx->cfg.M * ctx->cfg.M;
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_thr, ctx->h_thr.data(), mm * sizeof(uint32_t), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_last, ctx->h_last.data(), ctx->cfg.M * sizeof(int32_t), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_w, ctx->h_w.data(), mm * sizeof(float), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return NETMAX_OK;
+}
+
+static int rebuild_policy(netmax_ctx *ctx, const double *P, double alpha, double rho)
+{
+    std::vector<uint32_t> thr;
+    std::vector<int32_t> last;
+    std::vector<float> w;
+    std::string why;
+    const int rc = build_tables(ctx->cfg.M, P, ctx->has_adj ? ctx->adj.data() : nullptr, alpha, rho,
+                                ctx->cfg.strict_o3 != 0, thr, last, w, why);
+    if (rc != NETMAX_OK) return fail(ctx, rc, why);
+    // the stream may still read the old tables: wait before they are overwritten
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->h_thr.swap(thr);
+    ctx->h_last.swap(last);
+    ctx->h_w.swap(w);
+    return upload_tables(ctx);
+}
+
+static void release(netmax_ctx *ctx)
+{
+    (void)hipFree(ctx->d_thr); (void)hipFree(ctx->d_last); (void)hipFree(ctx->d_w);
+    (void)hipFree(ctx->d_row0); (void)hipFree(ctx->d_nrows); (void)hipFree(ctx->d_idx);
+    for (auto *p : ctx->d_act) (void)hipFree(p);
+    (void)hipFree(ctx->d_dz[0]); (void)hipFree(ctx->d_dz[1]);
+    (void)hipFree(ctx->d_loss); (void)hipFree(ctx->d_flag);
+    (void)hipFree(ctx->d_partial); (void)hipFree(ctx->d_cd);
+    delete ctx;
+}
+
+static int check_launch(netmax_ctx *ctx, const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ctx, NETMAX_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
+    return NETMAX_OK;
+}
+
+// --------------------------------------------------------------------------------------------------
+extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
+{
+    if (!out) return fail(nullptr, NETMAX_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!cfg || !cfg->P) return fail(nullptr, NETMAX_EINVAL, "cfg or cfg->P is NULL");
+    char buf[200];
+    if (cfg->M < 2 || cfg->M > 4096) return fail(nullptr, NETMAX_EINVAL, "M must be in 2..4096");
+    if (cfg->D < 1 || cfg->ld < cfg->D || cfg->ld % 64 != 0)
+        return fail(nullptr, NETMAX_EINVAL, "need 1 <= D <= ld and ld a multiple of 64");
+    if ((cfg->ld + 4095) / 4096 + 8 > (int64_t)0x7FFFFFFF / cfg->M)
+        return fail(nullptr, NETMAX_EINVAL, "M * ld is too large for one launch");
+    if (!(cfg->lr > 0.0f) || !(cfg->momentum >= 0.0f) || !(cfg->momentum < 1.0f) || !(cfg->weight_decay >= 0.0f) ||
+        !(cfg->rho >= 0.0f))
+        return fail(nullptr, NETMAX_EINVAL, "need lr > 0, 0 <= momentum < 1, weight_decay >= 0, rho >= 0");
+    if (cfg->model != NETMAX_FLAT && cfg->model != NETMAX_MLP) return fail(nullptr, NETMAX_EINVAL, "unknown model kind");
+    if (cfg->gemm_in != NETMAX_F32 && cfg->gemm_in != NETMAX_BF16) return fail(nullptr, NETMAX_EINVAL, "unknown gemm_in");
+
+    netmax_ctx *ctx = new (std::nothrow) netmax_ctx;
+    if (!ctx) return fail(nullptr, NETMAX_ENOMEM, "out of host memory");
+    ctx->cfg = *cfg;
+    ctx->cfg.P = nullptr;
+    ctx->cfg.adj = nullptr;
+    ctx->stream = (hipStream_t)cfg->stream;
+    const int M = cfg->M;
+    const size_t mm = (size_t)M * M;
+
+    if (cfg->model == NETMAX_MLP) {
+        if (cfg->n_layers < 1 || cfg->n_layers > NETMAX_MAX_LAYERS || cfg->batch < 1 || cfg->batch > 1024) {
+            release(ctx);
+            return fail(nullptr, NETMAX_EINVAL, "MLP needs 1 <= n_layers <= 7 and 1 <= batch <= 1024");
+        }
+        int64_t off = 0;
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            if (cfg->dims[l] < 1 || cfg->dims[l + 1] < 1 || cfg->dims[l] > (1 << 24) || cfg->dims[l + 1] > (1 << 24)) {
+                release(ctx);
+                return fail(nullptr, NETMAX_EINVAL, "layer widths must be in 1..2^24");
+            }
+            ctx->woff[l] = off;
+            off += cfg->dims[l] * cfg->dims[l + 1] + cfg->dims[l + 1];
+        }
+        if (off != cfg->D) {
+            snprintf(buf, sizeof buf, "D = %lld does not match the layer widths (%lld parameters)", (long long)cfg->D,
+                     (long long)off);
+            release(ctx);
+            return fail(nullptr, NETMAX_EINVAL, buf);
+        }
+    } else if (!(cfg->grad_sigma >= 0.0f)) {
+        release(ctx);
+        return fail(nullptr, NETMAX_EINVAL, "grad_sigma must be >= 0");
+    }
+
+    ctx->P.assign(cfg->P, cfg->P + mm);
+    if (cfg->adj) {
+        ctx->adj.assign(cfg->adj, cfg->adj + mm);
+        ctx->has_adj = true;
+    }
+    std::string why;
+    int rc = build_tables(M, ctx->P.data(), ctx->has_adj ? ctx->adj.data() : nullptr, (double)cfg->lr, (double)cfg->rho,
+                          cfg->strict_o3 != 0, ctx->h_thr, ctx->h_last, ctx->h_w, why);
+    if (rc != NETMAX_OK) {
+        release(ctx);
+        return fail(nullptr, rc, why);
+    }
+
+#define INIT_TRY(expr)                                                                                         \
+    do {                                                                                                       \
+        hipError_t e_ = (expr);                                                                                \
+        if (e_ != hipSuccess) {                                                                                \
+            std::string m_ = std::string(#expr) + ": " + hipGetErrorString(e_);                                \
+            release(ctx);                                                                                      \
+            return fail(nullptr, e_ == hipErrorOutOfMemory ? NETMAX_ENOMEM : NETMAX_EDEVICE, m_);              \
+        }                                                                                                      \
+    } while (0)
+
+    INIT_TRY(hipGetDevice(&ctx->device));
+    INIT_TRY(hipMalloc(&ctx->d_thr, mm * sizeof(uint32_t)));
+    INIT_TRY(hipMalloc(&ctx->d_last, M * sizeof(int32_t)));
+    INIT_TRY(hipMalloc(&ctx->d_w, mm * sizeof(float)));
+    INIT_TRY(hipMalloc(&ctx->d_partial, (size_t)consensus_partials(cfg->ld) * sizeof(double)));
+    INIT_TRY(hipMalloc(&ctx->d_cd, sizeof(double)));
+    if (cfg->model == NETMAX_MLP) {
+        const size_t MB = (size_t)M * cfg->batch;
+        int64_t widest = 0;
+        for (int l = 1; l <= cfg->n_layers; ++l) {
+            INIT_TRY(hipMalloc(&ctx->d_act[l], MB * cfg->dims[l] * sizeof(float)));
+            if (cfg->dims[l] > widest) widest = cfg->dims[l];
+        }
+        INIT_TRY(hipMalloc(&ctx->d_dz[0], MB * widest * sizeof(float)));
+        INIT_TRY(hipMalloc(&ctx->d_dz[1], MB * widest * sizeof(float)));
+        INIT_TRY(hipMalloc(&ctx->d_idx, MB * sizeof(int32_t)));
+        INIT_TRY(hipMalloc(&ctx->d_row0, M * sizeof(int64_t)));
+        INIT_TRY(hipMalloc(&ctx->d_nrows, M * sizeof(int32_t)));
+        INIT_TRY(hipMalloc(&ctx->d_loss, M * sizeof(float)));
+        INIT_TRY(hipMalloc(&ctx->d_flag, sizeof(int32_t)));
+    }
+#undef INIT_TRY
+    rc = upload_tables(ctx);
+    if (rc != NETMAX_OK) {
+        g_init_error = ctx->err;
+        release(ctx);
+        return rc;
+    }
+    *out = ctx;
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_build_tables(int32_t M, const double *P, const uint8_t *adj, float lr, float rho, int32_t strict_o3,
+                                   uint32_t *thresholds_host, int32_t *last_host, float *w_host)
+{
+    if (M < 2 || M > 4096 || !P || !thresholds_host || !last_host || !w_host || !(lr > 0.0f) || !(rho >= 0.0f))
+        return fail(nullptr, NETMAX_EINVAL, "bad argument");
+    std::vector<uint32_t> thr;
+    std::vector<int32_t> last;
+    std::vector<float> w;
+    std::string why;
+    const int rc = build_tables(M, P, adj, (double)lr, (double)rho, strict_o3 != 0, thr, last, w, why);
+    if (rc != NETMAX_OK) return fail(nullptr, rc, why);
+    memcpy(thresholds_host, thr.data(), thr.size() * sizeof(uint32_t));
+    memcpy(last_host, last.data(), last.size() * sizeof(int32_t));
+    memcpy(w_host, w.data(), w.size() * sizeof(float));
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_destroy(netmax_ctx *ctx)
+{
+    if (!ctx) return NETMAX_OK;
+    (void)hipStreamSynchronize(ctx->stream);
+    release(ctx);
+    return NETMAX_OK;
+}
+
+extern "C" const char *netmax_last_error(const netmax_ctx *ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+extern "C" int netmax_set_policy(netmax_ctx *ctx, const double *P, float rho)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!P || !(rho >= 0.0f)) return fail(ctx, NETMAX_EINVAL, "P is NULL or rho < 0");
+    const int rc = rebuild_policy(ctx, P, (double)ctx->cfg.lr, (double)rho);
+    if (rc != NETMAX_OK) return rc;
+    ctx->P.assign(P, P + (size_t)ctx->cfg.M * ctx->cfg.M);
+    ctx->cfg.rho = rho;
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_set_lr(netmax_ctx *ctx, float lr)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!(lr > 0.0f)) return fail(ctx, NETMAX_EINVAL, "lr must be > 0");
+    const int rc = rebuild_policy(ctx, ctx->P.data(), (double)lr, (double)ctx->cfg.rho);
+    if (rc != NETMAX_OK) return rc;
+    ctx->cfg.lr = lr;
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_bind_state(netmax_ctx *ctx, float *x_a, float *x_b, float *v, float *g)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!x_a || !x_b || !v || !g) return fail(ctx, NETMAX_EINVAL, "a state pointer is NULL");
+    if (x_a == x_b) return fail(ctx, NETMAX_EINVAL, "x_a and x_b must be different buffers");
+    for (const void *p : {(const void *)x_a, (const void *)x_b, (const void *)v, (const void *)g})
+        if ((uintptr_t)p % 16 != 0) return fail(ctx, NETMAX_EINVAL, "state pointers must be 16-byte aligned");
+    ctx->x_cur = x_a;
+    ctx->x_next = x_b;
+    ctx->v = v;
+    ctx->g = g;
+    return NETMAX_OK;
+}
+
+// Counts labels outside [0, C): one pass over the label array, any violation raises the flag.
+__global__ void __launch_bounds__(256) check_labels_kernel(int64_t n, int32_t C, const int32_t *__restrict__ labels,
+                                                           int32_t *__restrict__ flag)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n && (labels[t] < 0 || labels[t] >= C)) atomicOr(flag, 1);
+}
+
+extern "C" int netmax_bind_data(netmax_ctx *ctx, const void *feats, const int32_t *labels, const int64_t *shard_off)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (ctx->cfg.model != NETMAX_MLP) return fail(ctx, NETMAX_ESTATE, "data can only be bound to an MLP context");
+    if (!feats || !labels || !shard_off) return fail(ctx, NETMAX_EINVAL, "a data pointer is NULL");
+    const int M = ctx->cfg.M;
+    std::vector<int64_t> row0(M);
+    std::vector<int32_t> nrows(M);
+    if (shard_off[0] < 0) return fail(ctx, NETMAX_EINVAL, "shard_off[0] < 0");
+    for (int i = 0; i < M; ++i) {
+        const int64_t n = shard_off[i + 1] - shard_off[i];
+        if (n < 1 || n > 0x7FFFFFFFLL) return fail(ctx, NETMAX_EINVAL, "every shard needs 1 .. 2^31-1 rows");
+        row0[i] = shard_off[i];
+        nrows[i] = (int32_t)n;
+    }
+    const int64_t n_total = shard_off[M];
+    if (n_total > 0x7FFFFFFFLL * 256) return fail(ctx, NETMAX_EINVAL, "too many rows");
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_row0, row0.data(), M * sizeof(int64_t), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_nrows, nrows.data(), M * sizeof(int32_t), hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemsetAsync(ctx->d_flag, 0, sizeof(int32_t), ctx->stream));
+    hipLaunchKernelGGL(check_labels_kernel, dim3((unsigned)((n_total + 255) / 256)), dim3(256), 0, ctx->stream, n_total,
+                       (int32_t)ctx->cfg.dims[ctx->cfg.n_layers], labels, ctx->d_flag);
+    int rc = check_launch(ctx, "check_labels");
+    if (rc != NETMAX_OK) return rc;
+    int32_t flag = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&flag, ctx->d_flag, sizeof flag, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (flag) return fail(ctx, NETMAX_EINVAL, "a label is outside [0, number of classes)");
+    ctx->feats = feats;
+    ctx->labels = labels;
+    ctx->data_bound = true;
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_sample_peers(netmax_ctx *ctx, uint64_t iter, int32_t *peers_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!peers_dev) return fail(ctx, NETMAX_EINVAL, "peers_dev is NULL");
+    launch_sample_peers(ctx->stream, ctx->cfg.M, ctx->d_thr, ctx->d_last, ctx->cfg.seed, iter, peers_dev);
+    return check_launch(ctx, "sample_peers");
+}
+
+extern "C" int netmax_sample_batch(netmax_ctx *ctx, uint64_t iter, int32_t *idx_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (ctx->cfg.model != NETMAX_MLP || !ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
+    if (!idx_dev) return fail(ctx, NETMAX_EINVAL, "idx_dev is NULL");
+    launch_sample_batch(ctx->stream, ctx->cfg.M, ctx->cfg.batch, ctx->d_nrows, ctx->cfg.seed, iter, idx_dev);
+    return check_launch(ctx, "sample_batch");
+}
+
+extern "C" int netmax_local_step(netmax_ctx *ctx, uint64_t iter)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
+    const netmax_config &c = ctx->cfg;
+    if (c.model == NETMAX_FLAT) {
+        launch_synth_grad(ctx->stream, c.M, c.D, c.ld, c.grad_sigma, c.seed, iter, ctx->g);
+        return check_launch(ctx, "synth_grad");
+    }
+    if (!ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
+    launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
+    MlpPlan p{};
+    p.M = c.M; p.n_layers = c.n_layers; p.B = c.batch; p.ld = c.ld; p.bf16 = (c.gemm_in == NETMAX_BF16);
+    for (int l = 0; l <= c.n_layers; ++l) { p.dims[l] = c.dims[l]; p.woff[l] = ctx->woff[l]; p.act[l] = ctx->d_act[l]; }
+    p.feats = ctx->feats; p.labels = ctx->labels; p.row0 = ctx->d_row0; p.idx = ctx->d_idx;
+    p.dz[0] = ctx->d_dz[0]; p.dz[1] = ctx->d_dz[1]; p.loss = ctx->d_loss;
+    launch_mlp_grad(ctx->stream, p, ctx->x_cur, ctx->g);
+    return check_launch(ctx, "mlp_grad");
+}
+
+extern "C" int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
+    if (!peers_dev) return fail(ctx, NETMAX_EINVAL, "peers_dev is NULL");
+    (void)iter;
+    const netmax_config &c = ctx->cfg;
+    launch_mix(ctx->stream, c.M, c.ld, ctx->x_cur, ctx->g, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum,
+               c.weight_decay);
+    const int rc = check_launch(ctx, "mix");
+    if (rc != NETMAX_OK) return rc;
+    float *t = ctx->x_cur;
+    ctx->x_cur = ctx->x_next;
+    ctx->x_next = t;
+    ctx->iterations += 1;
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_consensus_dist(netmax_ctx *ctx, double *out_host)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
+    if (!out_host) return fail(ctx, NETMAX_EINVAL, "out_host is NULL");
+    const netmax_config &c = ctx->cfg;
+    launch_consensus(ctx->stream, c.M, c.D, c.ld, ctx->x_cur, ctx->d_partial, ctx->d_cd);
+    const int rc = check_launch(ctx, "consensus");
+    if (rc != NETMAX_OK) return rc;
+    HIP_TRY(ctx, hipMemcpyAsync(out_host, ctx->d_cd, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return NETMAX_OK;
+}
+
+extern "C" const float *netmax_params(const netmax_ctx *ctx) { return ctx ? ctx->x_cur : nullptr; }
+extern "C" const float *netmax_losses(const netmax_ctx *ctx) { return ctx ? ctx->d_loss : nullptr; }
+extern "C" uint64_t netmax_iteration(const netmax_ctx *ctx) { return ctx ? ctx->iterations : 0; }
+
+extern "C" int netmax_get_tables(netmax_ctx *ctx, uint32_t *thresholds_host, int32_t *last_host, float *w_host)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    const size_t mm = (size_t)ctx->cfg.M * ctx->cfg.M;
+    // read back what the device holds, so the caller sees the tables the kernels use
+    if (thresholds_host) HIP_TRY(ctx, hipMemcpyAsync(thresholds_host, ctx->d_thr, mm * sizeof(uint32_t), hipMemcpyDeviceToHost, ctx->stream));
+    if (last_host) HIP_TRY(ctx, hipMemcpyAsync(last_host, ctx->d_last, ctx->cfg.M * sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+    if (w_host) HIP_TRY(ctx, hipMemcpyAsync(w_host, ctx->d_w, mm * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return NETMAX_OK;
+}

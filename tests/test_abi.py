@@ -1,0 +1,75 @@
+"""The C-ABI library loads without a GPU, exports what include/netmax.h declares, and its host-side
+table builder agrees with the oracle bit for bit."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2009_05766_amd as nm
+from netmax_inputs import workload, policy_for, WORKLOAD_NAMES
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "netmax.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(netmax_[a-z_]+)\s*\(", hdr))
+    assert declared == set(nm.EXPORTS)
+    L = nm.load()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("name", WORKLOAD_NAMES)
+def test_host_tables_match_oracle(ora, name):
+    w = workload(name)
+    P, rho = policy_for(w)
+    lr = float(np.float32(w.lr))
+    thr, last, wt = nm.netmax_build_tables(P, None, lr, rho)
+    T, l = ora.thresholds(P)
+    assert np.array_equal(thr, T) and np.array_equal(last, l)
+    np.testing.assert_allclose(wt, ora.mix_weights(P, None, lr, rho), rtol=1e-7, atol=0)
+
+
+def test_host_tables_with_adjacency_and_zero_rows(ora):
+    rng = np.random.default_rng(0)
+    M = 9
+    adj = (rng.random((M, M)) < 0.5).astype(np.uint8)
+    adj = np.maximum(adj, adj.T)
+    np.fill_diagonal(adj, 0)
+    for i in range(M):
+        adj[i, (i + 1) % M] = adj[(i + 1) % M, i] = 1
+    P = rng.random((M, M)) * adj
+    P /= P.sum(1, keepdims=True)
+    rho = float(np.float32(P[P > 0].min() / (4 * 0.1)))
+    thr, last, wt = nm.netmax_build_tables(P, adj, 0.1, rho, strict_o3=True)
+    T, l = ora.thresholds(P)
+    assert np.array_equal(thr, T) and np.array_equal(last, l)
+    np.testing.assert_allclose(wt, ora.mix_weights(P, adj, float(np.float32(0.1)), rho), rtol=1e-7)
+
+
+def test_host_table_errors():
+    P = np.full((3, 3), 1 / 3)
+    bad = P.copy(); bad[1] = [0.5, 0.6, -0.1]
+    with pytest.raises(nm.NetmaxError) as e:
+        nm.netmax_build_tables(bad, None, 0.1, 0.1)
+    assert e.value.code == nm.NETMAX_EINVAL
+    bad = P.copy(); bad[2] = [0.3, 0.3, 0.3]
+    with pytest.raises(nm.NetmaxError) as e:
+        nm.netmax_build_tables(bad, None, 0.1, 0.1)
+    assert e.value.code == nm.NETMAX_EINVAL and "sums to" in str(e.value)
+    P2 = np.array([[0, 0.999, 0.001], [0.5, 0, 0.5], [0.5, 0.5, 0]])
+    with pytest.raises(nm.NetmaxError) as e:     # w = 0.1 * 0.02 / 0.001 = 2 >= 1
+        nm.netmax_build_tables(P2, None, 0.1, 0.02)
+    assert e.value.code == nm.NETMAX_EINFEASIBLE
+    with pytest.raises(nm.NetmaxError) as e:     # w = 0.1*0.006/0.001 = 0.6: fine unless strict
+        nm.netmax_build_tables(P2, None, 0.1, 0.006, strict_o3=True)
+    assert e.value.code == nm.NETMAX_EINFEASIBLE
+    nm.netmax_build_tables(P2, None, 0.1, 0.006, strict_o3=False)
+    adj = np.ones((3, 3), np.uint8) - np.eye(3, dtype=np.uint8)
+    adj[0, 2] = adj[2, 0] = 0
+    with pytest.raises(nm.NetmaxError) as e:     # positive probability on a non-edge, constraint (o4)
+        nm.netmax_build_tables(P2, adj, 0.1, 0.001)
+    assert e.value.code == nm.NETMAX_EINVAL

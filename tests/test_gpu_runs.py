@@ -1,0 +1,241 @@
+"""GPU parity over whole runs: the five workloads, per step from identical state and as T-step free runs."""
+import numpy as np
+import pytest
+import torch
+
+from netmax_inputs import workload
+from harness import inputs_of, make_gpu, make_oracle, rel_err_rows
+
+pytestmark = pytest.mark.gpu
+
+# tolerances on the parameters, relative L2 per worker
+TOL_STEP, TOL_RUN = 1e-5, 1e-4
+
+
+def _sync_oracle_from_gpu(gpu, o):
+    o.X[:] = gpu.params().cpu().numpy()
+    o.V[:] = gpu.v.cpu().numpy()
+
+
+def _free_run(w, T, ora_threads=8, cd_rel=1e-3):
+    import oracle
+    oracle.set_threads(ora_threads)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp)
+    cd0 = gpu.consensus_dist()
+    assert cd0 == pytest.approx(o.consensus_dist(), rel=1e-6)
+    worst = 0.0
+    for it in range(T):
+        gpu.step(it)
+        peer = o.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), peer)
+    X = gpu.params().cpu().numpy()
+    err = rel_err_rows(X, o.X)
+    cd = gpu.consensus_dist()
+    assert cd == pytest.approx(o.consensus_dist(), rel=cd_rel)
+    assert np.all(X[:, w.D:] == 0)
+    oracle.set_threads(1)
+    gpu.close()
+    return err, cd0, cd
+
+
+def _stepwise(w, T, tol, ora_threads=8):
+    import oracle
+    oracle.set_threads(ora_threads)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp)
+    worst = 0.0
+    for it in range(T):
+        _sync_oracle_from_gpu(gpu, o)
+        gpu.step(it)
+        peer = o.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), peer)
+        worst = max(worst, rel_err_rows(gpu.params().cpu().numpy(), o.X))
+        assert worst < tol, (it, worst)
+    oracle.set_threads(1)
+    gpu.close()
+    return worst
+
+
+def _windows(w, T, K, tol, ora_threads=8, operands_bf16=False):
+    """The whole horizon T in windows of K steps: at the start of each window the oracle takes over the
+    GPU's state, then both run K steps freely.  Needed for ReLU networks: a hidden pre-activation within
+    rounding distance of zero gets derivative 0 on one side and 1 on the other, a discontinuous change of
+    the gradient (about 1/sqrt(batch * active units) of its norm) that no summation order can avoid and
+    that the dynamics then amplify.  Returns the worst end-of-window error."""
+    import oracle
+    oracle.set_threads(ora_threads)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp, operands_bf16=operands_bf16)
+    worst = 0.0
+    for it in range(T):
+        if it % K == 0:
+            _sync_oracle_from_gpu(gpu, o)
+        gpu.step(it)
+        peer = o.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), peer)
+        if (it + 1) % K == 0 or it + 1 == T:
+            e = rel_err_rows(gpu.params().cpu().numpy(), o.X)
+            worst = max(worst, e)
+            assert e < tol, (it, e)
+    oracle.set_threads(1)
+    gpu.close()
+    return worst
+
+
+def test_cfg1_full_run():
+    w = workload("cfg1")
+    assert _stepwise(w, 20, TOL_STEP) < TOL_STEP
+    err, cd0, cd = _free_run(w, w.T)
+    assert err < TOL_RUN, err
+    assert cd < cd0
+
+
+def test_cfg2_full_shape():
+    w = workload("cfg2")
+    assert _stepwise(w, 10, TOL_STEP) < TOL_STEP
+    assert _windows(w, 120, 20, TOL_RUN) < TOL_RUN
+
+
+def test_cfg2_reduced_shape_full_T():
+    w = workload("cfg2", dims=(64, 48, 10), n_per_worker=512)
+    assert _windows(w, w.T, 50, TOL_RUN) < TOL_RUN
+    err, cd0, cd = _free_run(w, w.T, cd_rel=0.1)
+    print(f"cfg2 reduced shape, free run of {w.T} steps: relative error {err:.3e}")
+    assert err < 5e-2, err          # sanity only: ReLU kinks make long free runs drift apart (see _windows)
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4"])
+def test_flat_reduced_shape_full_T(name):
+    w = workload(name, D=2**16)
+    assert _stepwise(w, 5, TOL_STEP) < TOL_STEP
+    err, cd0, cd = _free_run(w, w.T)
+    assert err < TOL_RUN, err
+
+
+TOL_BF16 = 2e-2
+# bf16 operands against the oracle with the same operand rounding, over a window of several steps: an
+# activation that fp32 and double accumulation place on different sides of a bf16 rounding boundary
+# differs by one bf16 ulp (2^-8 of that element); with ~1e5 activations per step that happens every
+# step, so windows drift faster than in the fp32 workloads while staying far below the bf16 tolerance.
+TOL_RUN_BF16_SAME = 1e-3
+
+
+def test_cfg5_reduced_shape():
+    w = workload("cfg5", M=8, n_per_worker=512, dims=(3072, 256, 128, 10))
+    # against the oracle with the same bf16 operands: fp32 tolerances per step and per window
+    assert _windows(w, 10, 1, TOL_STEP, operands_bf16=True) < TOL_STEP
+    assert _windows(w, 40, 10, TOL_RUN_BF16_SAME, operands_bf16=True) < TOL_RUN_BF16_SAME
+    # against exact arithmetic: the bf16 tolerance, per step and over a free run
+    assert _stepwise(w, 3, TOL_BF16) < TOL_BF16
+    err, cd0, cd = _free_run(w, 40, cd_rel=0.1)
+    assert err < TOL_BF16, err
+
+
+def test_cfg5_all_workers_tiny_layers_full_T():
+    w = workload("cfg5", n_per_worker=64, dims=(48, 32, 16, 10), batch=16)
+    assert _windows(w, w.T, 5, TOL_RUN_BF16_SAME, operands_bf16=True) < TOL_RUN_BF16_SAME
+    assert _windows(w, w.T, 50, TOL_BF16) < TOL_BF16             # against exact arithmetic
+    err, cd0, cd = _free_run(w, w.T, cd_rel=0.2)
+    print(f"cfg5 tiny layers, free run of {w.T} steps against exact arithmetic: relative error {err:.3e}")
+    assert err < 0.1, err           # sanity only: operand rounding plus ReLU kinks over 500 free steps
+
+
+def test_cfg5_full_shape_sampled_workers():
+    """cfg5 at its full layer widths, batch and worker count, in the launch configuration of the
+    benchmark (shards shortened to 256 images to keep host data generation short).  The oracle
+    recomputes the gradient and the update of a few sampled workers and their peers' rows."""
+    import oracle
+    from harness import hyper
+    w = workload("cfg5", n_per_worker=256)
+    inp = inputs_of(w)
+    h = hyper(w, inp["rho"])
+    gpu = make_gpu(w, inp)
+    oracle.set_threads(8)
+    T, last = oracle.thresholds(inp["P"])
+    wtab = oracle.mix_weights(inp["P"], None, h["lr"], h["rho"])
+    gpu.step(0)
+    peers = gpu.peers.cpu().numpy()
+    assert np.array_equal(peers, oracle.sample_peers(T, last, w.seed, 0))
+    idx = oracle.sample_batch(w.M, w.batch, inp["shard_off"], w.seed, 0)
+    G, X1 = gpu.g.cpu().numpy(), gpu.params().cpu().numpy()
+    for i in (0, 37, 127):
+        s, e = inp["shard_off"][i], inp["shard_off"][i + 1]
+        for same, tol in ((True, 1e-3), (False, 8e-2)):
+            g, _ = oracle.grad_mlp(w.dims, inp["X0"][i], inp["feats"][s:e], inp["labels"][s:e], idx[i],
+                                   operands_bf16=same)
+            assert rel_err_rows(G[i:i + 1, :w.D], g[None, :]) < tol
+        # the update of worker i from the oracle's exact-arithmetic gradient and its peer's row
+        m = int(peers[i])
+        sub = np.stack([inp["X0"][i], inp["X0"][m]])
+        gsub = np.zeros_like(sub)
+        gsub[0, :w.D] = g
+        vsub = np.zeros_like(sub)
+        wpair = np.zeros((2, 2))
+        wpair[0, 1] = wtab[i, m]
+        out = oracle.mix(sub, gsub, vsub, np.array([1, 1], np.int32), wpair, h["lr"], h["momentum"], h["weight_decay"])
+        assert rel_err_rows(X1[i:i + 1], out[0:1]) < 1e-4     # far inside the bf16 tolerance: only alpha * g carries its noise
+    oracle.set_threads(1)
+    gpu.close()
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4"])
+def test_flat_full_shape_sampled_columns(name):
+    """Full-size run in the benchmark's launch configuration.  The update is separable by column, so
+    the oracle recomputes windows of columns (start, chunk boundaries, ragged end) for all workers."""
+    import oracle
+    w = workload(name)
+    T = 4
+    P, rho = __import__("netmax_inputs").policy_for(w)
+    M, ld = w.M, w.ld
+    g = torch.Generator(device="cuda").manual_seed(7)
+    # x^0 generated on the device (a seeded stand-in of init_params at this size), then read back by window
+    base = torch.randn(ld, device="cuda", generator=g) * 0.1
+    X0 = base[None, :] + 0.01 * torch.randn((M, ld), device="cuda", generator=g)
+    import paper_2009_05766_amd as nm
+    from harness import hyper
+    gpu = nm.NetMax(M=M, D=w.D, ld=ld, model=nm.NETMAX_FLAT, seed=w.seed, P=P, **hyper(w, rho))
+    gpu.x_a.copy_(X0)
+    del X0, base
+    windows = [0, 4096 - 64, 4096 * 8 * 5 - 128, (ld // 2) // 4 * 4, ld - 4096 - 64, ld - 256]
+    width = 256
+    oracles = []
+    for c0 in windows:
+        x0 = gpu.x_a[:, c0:c0 + width].cpu().numpy().copy()
+        oracles.append(oracle.Oracle(M=M, ld=width, D=width, dims=(), batch=0, seed=w.seed, P=P, X0=x0, col0=c0,
+                                     **hyper(w, rho)))
+    for it in range(T):
+        gpu.step(it)
+        peers = gpu.peers.cpu().numpy()
+        for o in oracles:
+            assert np.array_equal(o.step(it), peers)
+    X = gpu.params()
+    for c0, o in zip(windows, oracles):
+        got = X[:, c0:c0 + width].cpu().numpy()
+        assert rel_err_rows(got, o.X) < TOL_STEP * T
+        assert rel_err_rows(gpu.v[:, c0:c0 + width].cpu().numpy(), o.V) < TOL_STEP * T
+    # consensus distance at full size against torch on the device, in double
+    Xd = X.double()
+    want = float(((Xd - Xd.mean(0, keepdim=True)) ** 2).sum())
+    assert gpu.consensus_dist() == pytest.approx(want, rel=1e-9)
+    gpu.close()
+
+
+def test_checkpoint_resume_is_bit_exact():
+    w = workload("cfg4", D=10000, T=20)
+    inp = inputs_of(w)
+    a = make_gpu(w, inp)
+    for it in range(20):
+        a.step(it)
+    b = make_gpu(w, inp)
+    for it in range(10):
+        b.step(it)
+    Xh, Vh = b.params().cpu().numpy().copy(), b.v.cpu().numpy().copy()
+    b.close()
+    c = make_gpu(w, dict(inp, X0=Xh))
+    c.v.copy_(torch.from_numpy(Vh))
+    for it in range(10, 20):
+        c.step(it)
+    assert np.array_equal(a.params().cpu().numpy(), c.params().cpu().numpy())
+    assert np.array_equal(a.v.cpu().numpy(), c.v.cpu().numpy())
+    a.close(); c.close()

@@ -78,7 +78,8 @@ def test_synthetic_gradient_follows_box_muller_of_the_words(ora):
     g = ora.synth_grad(1, 16, 64, sigma, 77, 9)
     for blk in range(4):
         r = _draw(ora, 77, 2, blk, 0, 9).astype(np.float64)
-        u = (np.floor(r / 256.0) + 0.5) / 2**24
+        u = (np.floor(r / 512.0) + 0.5) / 2**23
+        assert np.all(u.astype(np.float32).astype(np.float64) == u) and np.all((u > 0) & (u < 1))
         for h in range(2):
             rad = np.sqrt(-2 * np.log(u[2 * h]))
             want = sigma * rad * np.array([np.cos(2 * np.pi * u[2 * h + 1]), np.sin(2 * np.pi * u[2 * h + 1])])
