@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the NetMax iteration on one MI355X.
+
+A step is one pass of the whole hot path over all M workers: peer sampling, local gradient
+(synthetic for the flat workloads, grouped-GEMM perceptron gradient otherwise) and the fused
+momentum apply + mix.  Prints ONE JSON line: whole-job worker-iterations/s, the HBM roofline of the
+dominant kernel (mix) measured live with events on the launch stream, and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# Algorithmic HBM bytes per (worker, parameter) of the mix kernel with momentum: read x, v, g; write x', v'.
+# The peer's row is a second read of a row of x that some workgroup of the same column chunk also reads as
+# its own, so the minimum HBM traffic counts x once: 5 * 4 = 20 B.  (Counting the peer read too gives 24 B.)
+MIX_BYTES_MIN, MIX_BYTES_NAIVE = 20, 24
+
+
+def describe(w) -> str:
+    if w.model == "flat":
+        return (f"{w.name}: M={w.M} workers, flat fp32 parameter vector D={w.D}, synthetic N(0,1e-3) gradients, "
+                f"momentum {w.momentum} + consensus mix, links {w.links}")
+    return (f"{w.name}: M={w.M} workers, MLP {'-'.join(map(str, w.dims))}, batch {w.batch}, {w.gemm_in} GEMM operands, "
+            f"momentum {w.momentum} + consensus mix, links {w.links}")
+
+
+def cpu_baseline(w, inp, budget_s: float = 12.0):
+    """The oracle as it stands, on a bounded sample of the workload, single-threaded."""
+    import numpy as np
+    import oracle
+    from netmax_inputs import hyperparameters
+    h = hyperparameters(w, inp["rho"])
+    oracle.set_threads(1)
+    if w.model == "flat":
+        cols = min(w.ld, 1 << 19)
+        X0 = np.ascontiguousarray(inp["X0"][:, :cols])
+        o = oracle.Oracle(M=w.M, ld=cols, D=cols, dims=(), batch=0, seed=w.seed, P=inp["P"], X0=X0, **h)
+        scale = w.ld / cols
+        sample = f"all {w.M} workers, first {cols} of {w.ld} columns"
+    else:
+        o = oracle.Oracle(M=w.M, ld=w.ld, D=w.D, dims=w.dims, batch=w.batch, seed=w.seed, P=inp["P"], X0=inp["X0"],
+                          feats=inp["feats"], labels=inp["labels"], shard_off=inp["shard_off"], **h)
+        scale = 1.0
+        sample = f"all {w.M} workers, full shape"
+    t0 = time.perf_counter()
+    o.step(0)
+    t1 = time.perf_counter() - t0
+    iters = max(1, min(int(budget_s / max(t1, 1e-9)), 50))
+    t0 = time.perf_counter()
+    for it in range(1, 1 + iters):
+        o.step(it)
+    dt = (time.perf_counter() - t0) / iters
+    return {"value": w.M / (dt * scale), "unit": "worker-iterations/s", "cores": 1, "kind": "oracle",
+            "sample": f"{sample}, {iters} iterations timed, scaled to the full row length"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3", help="cfg1..cfg5 (default: cfg3, the HBM-bound ResNet18-sized mix)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0,
+                    help="before the timed region, run this many plain device copies of the parameter matrix "
+                         "(a kernel of known traffic, used to scale profiler byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, nothing sharded); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2009_05766_amd as nm
+    from netmax_inputs import workload, policy_for, make_shards, init_params, hyperparameters as hyper
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    w = workload(args.workload)
+    t_in = time.perf_counter()
+    P, rho = policy_for(w)
+    feats, labels, shard_off = make_shards(w)
+    X0 = init_params(w)
+    inp = dict(P=P, rho=rho, feats=feats, labels=labels, shard_off=shard_off, X0=X0)
+    print(f"[bench] inputs of {w.name} generated in {time.perf_counter() - t_in:.1f} s", file=sys.stderr, flush=True)
+
+    gpu = nm.NetMax(M=w.M, D=w.D, ld=w.ld, model=nm.NETMAX_FLAT if w.model == "flat" else nm.NETMAX_MLP, dims=w.dims,
+                    batch=w.batch, gemm_in=nm.NETMAX_BF16 if w.gemm_in == "bf16" else nm.NETMAX_F32, seed=w.seed, P=P,
+                    X0=X0, feats=feats, labels=labels, shard_off=shard_off, **hyper(w, rho))
+    torch.cuda.synchronize()
+    cd0 = gpu.consensus_dist()
+
+    for it in range(args.warmup):
+        gpu.step(it)
+    torch.cuda.synchronize()
+
+    for _ in range(args.copy_probe):
+        gpu.x_b.copy_(gpu.x_a) if gpu.params() is gpu.x_a else gpu.x_a.copy_(gpu.x_b)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        it = args.warmup + k
+        e = ev[k]
+        e[0].record()
+        nm.netmax_sample_peers(gpu.ctx, it, gpu.peers)
+        e[1].record()
+        nm.netmax_local_step(gpu.ctx, it)
+        e[2].record()
+        nm.netmax_mix(gpu.ctx, it, gpu.peers)
+        e[3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in ev])   # sample, grad, mix
+    ms_sample, ms_grad, ms_mix = ms.mean(axis=0)
+    cd1 = gpu.consensus_dist()
+    ms_per_step = wall * 1e3 / K
+    value = w.M * K / wall
+
+    elems = w.M * w.ld
+    mix_s = ms_mix * 1e-3
+    achieved = MIX_BYTES_MIN * elems / mix_s / 1e9
+    roofline = {"bound": "hbm", "kernel": "mix_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "bytes_per_worker_param": MIX_BYTES_MIN, "avg_launch_ms": float(ms_mix),
+                "achieved_counting_peer_read": MIX_BYTES_NAIVE * elems / mix_s / 1e9}
+
+    out = {"metric": "worker-iterations/sec (sample+grad+mix)", "value": value, "unit": "worker-iterations/s",
+           "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_in == "bf16" else "f32",
+           "data": "synthetic", "config": {"workload": describe(w), "M": w.M, "D": w.D, "iterations": K},
+           "phase_ms": {"sample_peers": float(ms_sample), "local_step": float(ms_grad), "mix": float(ms_mix)},
+           "consensus_distance": {"before": cd0, "after": cd1},
+           "roofline": roofline}
+    gpu.close()
+    del gpu
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

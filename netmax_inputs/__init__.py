@@ -7,7 +7,7 @@ sampling, thresholds, gradients, mixing, consensus distance) lives here; both
 the HIP library and the CPU oracle receive what these functions return as plain
 arrays.
 """
-from .configs import Workload, workload, WORKLOAD_NAMES, BASE_SEED  # noqa: F401
+from .configs import Workload, workload, WORKLOAD_NAMES, BASE_SEED, hyperparameters  # noqa: F401
 from .policy import (  # noqa: F401
     policy_from_speeds,
     floor_and_renormalise,

@@ -114,3 +114,11 @@ def workload(name: str, *, M: Optional[int] = None, D: Optional[int] = None,
         kw["D"] = D
         kw["ld"] = _round_up(D, 64)
     return replace(w, **kw) if kw else w
+
+
+def hyperparameters(w: Workload, rho: float) -> dict:
+    """The scalar hyper-parameters as the single-precision values both implementations receive."""
+    import numpy as np
+    f = lambda v: float(np.float32(v))
+    return dict(lr=f(w.lr), momentum=f(w.momentum), weight_decay=f(w.weight_decay), rho=f(rho),
+                grad_sigma=f(w.grad_sigma))

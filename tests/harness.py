@@ -3,7 +3,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from netmax_inputs import Workload, policy_for, make_shards, init_params
+from netmax_inputs import Workload, policy_for, make_shards, init_params, hyperparameters
 
 
 def inputs_of(w: Workload):
@@ -14,9 +14,7 @@ def inputs_of(w: Workload):
 
 
 def hyper(w: Workload, rho: float):
-    f = lambda v: float(np.float32(v))
-    return dict(lr=f(w.lr), momentum=f(w.momentum), weight_decay=f(w.weight_decay), rho=f(rho),
-                grad_sigma=f(w.grad_sigma))
+    return hyperparameters(w, rho)
 
 
 def make_gpu(w: Workload, inp, **over):
