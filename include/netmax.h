@@ -18,8 +18,14 @@
  *     "device" pointers are HIP device memory owned by the caller, who keeps it
  *     alive while the context uses it.  The library owns only its own tables and
  *     scratch (thresholds, weights, batch indices, activations, partial sums).
- *   - Matrices over workers are row-major [M][ld] floats, ld >= D, ld a multiple
- *     of 64, base pointers 16-byte aligned.  Columns D..ld-1 are padding and stay 0.
+ *   - Matrices over workers (x, v, g) are M x ld floats, ld >= D a multiple of
+ *     NETMAX_TILE, base pointers 16-byte aligned, in the WORKER-INTERLEAVED TILE
+ *     LAYOUT: [ld / NETMAX_TILE tiles][M workers][NETMAX_TILE floats], i.e. column j
+ *     of worker i is element ((j / NETMAX_TILE) * M + i) * NETMAX_TILE + j % NETMAX_TILE.
+ *     (All workers' copies of a column tile are contiguous, so the mix kernel sweeps
+ *     HBM linearly and finds a peer's row next to the worker's own.)  netmax_pack
+ *     and netmax_unpack convert from and to row-major.  Columns D..ld-1 are padding
+ *     and stay 0.
  *   - Kernels are enqueued on the hipStream_t given at init and calls return
  *     without waiting, except netmax_consensus_dist, netmax_set_policy,
  *     netmax_set_lr, netmax_get_tables and netmax_destroy, which synchronise
@@ -38,6 +44,7 @@ extern "C" {
 #endif
 
 #define NETMAX_MAX_LAYERS 7
+#define NETMAX_TILE 2048 /* floats per column tile and worker */
 
 typedef struct netmax_ctx netmax_ctx; /* opaque, library-owned */
 
@@ -56,7 +63,7 @@ typedef enum { NETMAX_F32 = 0, NETMAX_BF16 = 1 } netmax_dtype;
 typedef struct {
     int32_t M;         /* workers, 2 .. 4096 */
     int64_t D;         /* parameters per worker */
-    int64_t ld;        /* row length of X, V, G: >= D, multiple of 64 */
+    int64_t ld;        /* padded number of columns of x, v, g: >= D, multiple of NETMAX_TILE */
     int32_t model;     /* netmax_model. FLAT: the local gradient is synthetic N(0, grad_sigma^2) noise.
                           MLP: ReLU perceptron with softmax cross-entropy; one layer = softmax regression */
     int32_t n_layers;  /* MLP only: 1 .. NETMAX_MAX_LAYERS */
@@ -97,7 +104,7 @@ int netmax_set_policy(netmax_ctx *ctx, const double *P, float rho);
 /* Changes alpha (learning-rate decay, Section V-A) and rebuilds w, which depends on it. */
 int netmax_set_lr(netmax_ctx *ctx, float lr);
 
-/* Binds the caller's state, all device float [M][ld]: x_a holds x^t for the next iteration to run and
+/* Binds the caller's state, all device float M x ld in the tile layout: x_a holds x^t for the next iteration to run and
  * x_b receives x^{t+1} (the two swap roles after every netmax_mix); v is the momentum buffer (the caller
  * zeroes it for v^0 = 0), g receives the gradients. */
 int netmax_bind_state(netmax_ctx *ctx, float *x_a, float *x_b, float *v, float *g);
@@ -106,6 +113,12 @@ int netmax_bind_state(netmax_ctx *ctx, float *x_a, float *x_b, float *v, float *
  * labels: device int32 [n_total], values in [0, dims[n_layers]); shard_off: host int64 [M+1], worker i
  * owns rows shard_off[i] .. shard_off[i+1]-1 (each shard non-empty, at most 2^31-1 rows). */
 int netmax_bind_data(netmax_ctx *ctx, const void *feats, const int32_t *labels, const int64_t *shard_off);
+
+/* Layout conversion on the context's stream.  rows_dev: device float, row-major [M][row_ld], row_ld >= D;
+ * tiled_dev: device float M x ld in the tile layout.  netmax_pack copies the first D columns of every row
+ * and zeroes the padding; netmax_unpack writes the first D columns of every row. */
+int netmax_pack(netmax_ctx *ctx, const float *rows_dev, int64_t row_ld, float *tiled_dev);
+int netmax_unpack(netmax_ctx *ctx, const float *tiled_dev, float *rows_dev, int64_t row_ld);
 
 /* Peer selection of Algorithm 2 for all workers at iteration `iter`: worker i draws word 0 of block 0 of
  * stream 0 and takes the first m whose cumulative threshold exceeds it.  peers_dev: device int32 [M]. */
@@ -133,7 +146,7 @@ int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev);
  * order.  Waits for the stream; out_host: host double. */
 int netmax_consensus_dist(netmax_ctx *ctx, double *out_host);
 
-/* Device pointer of the current parameters x^t (one of x_a, x_b), NULL if nothing is bound. */
+/* Device pointer of the current parameters x^t (one of x_a, x_b; tile layout), NULL if nothing is bound. */
 const float *netmax_params(const netmax_ctx *ctx);
 
 /* MLP only: device float [M], mean batch loss of each worker as computed by the last netmax_local_step. */

@@ -17,6 +17,7 @@ from dataclasses import dataclass, replace
 from typing import Optional, Tuple
 
 BASE_SEED = 20090576  # per-purpose seeds are offsets from this
+PAD = 2048            # rows are padded with zeros to a multiple of this many columns
 
 
 def _round_up(x: int, m: int) -> int:
@@ -31,7 +32,7 @@ class Workload:
     model: str                  # "flat" | "mlp"  (softmax regression = 1-layer mlp)
     dims: Tuple[int, ...]       # layer widths, () for flat
     D: int                      # parameters per worker
-    ld: int                     # padded row length (multiple of 64)
+    ld: int                     # padded row length (multiple of PAD = 2048)
     batch: int                  # 0 for flat
     n_per_worker: int           # samples in each worker's shard, 0 for flat
     lr: float
@@ -62,7 +63,7 @@ def _mk(name, index, M, model, dims, D, batch, n, lr, mu, sigma, gemm_in, T, lin
     if model == "mlp":
         D = mlp_param_count(dims)
     return Workload(name=name, index=index, M=M, model=model, dims=tuple(dims), D=D,
-                    ld=_round_up(D, 64), batch=batch, n_per_worker=n, lr=lr, momentum=mu,
+                    ld=_round_up(D, PAD), batch=batch, n_per_worker=n, lr=lr, momentum=mu,
                     weight_decay=0.0, grad_sigma=sigma, gemm_in=gemm_in, T=T, links=links,
                     data=data, floor_policy=floor)
 
@@ -108,11 +109,11 @@ def workload(name: str, *, M: Optional[int] = None, D: Optional[int] = None,
         assert w.model == "mlp"
         kw["dims"] = tuple(dims)
         kw["D"] = mlp_param_count(tuple(dims))
-        kw["ld"] = _round_up(kw["D"], 64)
+        kw["ld"] = _round_up(kw["D"], PAD)
     if D is not None:
         assert w.model == "flat"
         kw["D"] = D
-        kw["ld"] = _round_up(D, 64)
+        kw["ld"] = _round_up(D, PAD)
     return replace(w, **kw) if kw else w
 
 

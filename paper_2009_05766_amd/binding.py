@@ -14,13 +14,14 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libnetmax.so")
 
 NETMAX_MAX_LAYERS = 7
+NETMAX_TILE = 2048
 NETMAX_OK, NETMAX_EINVAL, NETMAX_EINFEASIBLE, NETMAX_ESTATE, NETMAX_EDEVICE, NETMAX_ENOMEM = range(6)
 NETMAX_FLAT, NETMAX_MLP = 0, 1
 NETMAX_F32, NETMAX_BF16 = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix",
     "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -64,6 +65,8 @@ def load():
         "netmax_set_lr": (C.c_int, [vp, f32]),
         "netmax_bind_state": (C.c_int, [vp, vp, vp, vp, vp]),
         "netmax_bind_data": (C.c_int, [vp, vp, vp, vp]),
+        "netmax_pack": (C.c_int, [vp, vp, i64, vp]),
+        "netmax_unpack": (C.c_int, [vp, vp, vp, i64]),
         "netmax_sample_peers": (C.c_int, [vp, u64, vp]),
         "netmax_sample_batch": (C.c_int, [vp, u64, vp]),
         "netmax_local_step": (C.c_int, [vp, u64]),
@@ -166,6 +169,16 @@ def netmax_bind_data(ctx, feats, labels, shard_off: np.ndarray):
     _check(load().netmax_bind_data(ctx, _dp(feats), _dp(labels, torch.int32), _hp(so)), ctx)
 
 
+def netmax_pack(ctx, rows, row_ld: int, tiled):
+    import torch
+    _check(load().netmax_pack(ctx, _dp(rows, torch.float32), row_ld, _dp(tiled, torch.float32)), ctx)
+
+
+def netmax_unpack(ctx, tiled, rows, row_ld: int):
+    import torch
+    _check(load().netmax_unpack(ctx, _dp(tiled, torch.float32), _dp(rows, torch.float32), row_ld), ctx)
+
+
 def netmax_sample_peers(ctx, it: int, peers):
     import torch
     _check(load().netmax_sample_peers(ctx, it, _dp(peers, torch.int32)), ctx)
@@ -218,12 +231,16 @@ def netmax_destroy(ctx):
 # ---- a holder for the device buffers of one run ---------------------------------------------------
 
 class NetMax:
-    """Owns the torch tensors (device memory) of one run and forwards every step to the library."""
+    """Owns the torch tensors (device memory) of one run and forwards every step to the library.
+
+    x_a, x_b, v, g are flat device tensors of M * ld floats in the library's worker-interleaved tile
+    layout; get()/set() convert from and to row-major [M, cols] through netmax_unpack / netmax_pack."""
 
     def __init__(self, *, M, D, ld, model, dims=(), batch=0, gemm_in=NETMAX_F32, lr, momentum=0.0,
                  weight_decay=0.0, rho, grad_sigma=0.0, seed, P, adj=None, strict_o3=False,
                  X0: Optional[np.ndarray] = None, feats=None, labels=None, shard_off=None, device="cuda:0"):
         import torch
+        assert ld % NETMAX_TILE == 0, "ld must be a multiple of NETMAX_TILE"
         self.M, self.D, self.ld, self.batch = M, D, ld, batch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
@@ -232,17 +249,14 @@ class NetMax:
                                momentum=momentum, weight_decay=weight_decay, rho=rho, grad_sigma=grad_sigma,
                                seed=seed, strict_o3=strict_o3, P=P, adj=adj, stream=self.stream)
         kw = dict(dtype=torch.float32, device=self.device)
-        self.x_a = torch.empty((M, ld), **kw)
-        self.x_b = torch.empty((M, ld), **kw)
-        self.v = torch.zeros((M, ld), **kw)
-        self.g = torch.zeros((M, ld), **kw)
-        if X0 is not None:
-            self.x_a.copy_(torch.from_numpy(np.ascontiguousarray(X0, dtype=np.float32)))
-        else:
-            self.x_a.zero_()
-        self.x_b.zero_()
+        self.x_a = torch.zeros(M * ld, **kw)
+        self.x_b = torch.zeros(M * ld, **kw)
+        self.v = torch.zeros(M * ld, **kw)
+        self.g = torch.zeros(M * ld, **kw)
         self.peers = torch.zeros(M, dtype=torch.int32, device=self.device)
         netmax_bind_state(self.ctx, self.x_a, self.x_b, self.v, self.g)
+        if X0 is not None:
+            self.set("x", X0)
         self.feats = self.labels = None
         if feats is not None:
             if isinstance(feats, np.ndarray):
@@ -255,6 +269,38 @@ class NetMax:
             self.feats, self.labels = feats.contiguous(), labels.contiguous()
             netmax_bind_data(self.ctx, self.feats, self.labels, shard_off)
 
+    # ---- state access --------------------------------------------------------------------------
+    def _buffer(self, name: str):
+        if name == "x":
+            return self.params()
+        return {"v": self.v, "g": self.g}[name]
+
+    def set(self, name: str, rows):
+        """Loads row-major [M, >= D] values (numpy or device tensor) into x (current), v or g."""
+        import torch
+        if isinstance(rows, np.ndarray):
+            rows = torch.from_numpy(np.ascontiguousarray(rows, dtype=np.float32)).to(self.device)
+        rows = rows.contiguous()
+        assert rows.shape[0] == self.M and rows.shape[1] >= self.D
+        netmax_pack(self.ctx, rows, rows.shape[1], self._buffer(name))
+        torch.cuda.current_stream(self.device).synchronize()   # `rows` may be a temporary
+
+    def get(self, name: str, cols: Optional[int] = None):
+        """Row-major device tensor [M, cols] of x (current), v or g; cols defaults to ld (padding as zeros)."""
+        import torch
+        cols = self.ld if cols is None else cols
+        out = torch.zeros((self.M, cols), dtype=torch.float32, device=self.device)
+        netmax_unpack(self.ctx, self._buffer(name), out, cols)
+        return out
+
+    def get_window(self, name: str, col0: int, width: int):
+        """Row-major [M, width] copy of columns col0 .. col0+width-1 (inside one tile) without a full unpack."""
+        assert col0 // NETMAX_TILE == (col0 + width - 1) // NETMAX_TILE
+        t, o = divmod(col0, NETMAX_TILE)
+        buf = self._buffer(name).view(self.ld // NETMAX_TILE, self.M, NETMAX_TILE)
+        return buf[t, :, o:o + width].contiguous()
+
+    # ---- the iteration -------------------------------------------------------------------------
     def sample_peers(self, it: int):
         netmax_sample_peers(self.ctx, it, self.peers)
         return self.peers
@@ -274,22 +320,22 @@ class NetMax:
         return netmax_consensus_dist(self.ctx)
 
     def params(self):
-        """The tensor that currently holds x^t."""
+        """The flat tile-layout tensor that currently holds x^t."""
         p = netmax_params(self.ctx)
         return self.x_a if p == self.x_a.data_ptr() else self.x_b
 
     def losses(self):
+        """Mean batch loss per worker of the last local step (device tensor [M]), None for flat models."""
         import torch
         p = netmax_losses(self.ctx)
         if not p:
             return None
         out = torch.empty(self.M, dtype=torch.float32, device=self.device)
-        # device-to-device copy of the library's buffer through HIP's runtime
-        import ctypes
-        hip = ctypes.CDLL("libamdhip64.so")
+        hip = C.CDLL("libamdhip64.so")
         torch.cuda.current_stream(self.device).synchronize()
         rc = hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(p), C.c_size_t(4 * self.M), C.c_int(3))
-        assert rc == 0
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpy of the loss vector failed with {rc}")
         return out
 
     def close(self):

@@ -2,26 +2,29 @@
 // One pass over X: per column, sums of d and d^2 with d = x_i - x_0 in double (shifting by the first
 // row removes the cancellation of the one-pass variance formula), CD_col = sum d^2 - (sum d)^2 / M.
 #include "kernels.h"
+#include "layout.h"
 #include "vec.h"
 
 namespace netmax {
 
 constexpr int CD_THREADS = 256;
 constexpr int CD_COLS = CD_THREADS * 4;
+static_assert(TILE % CD_COLS == 0, "a workgroup stays inside one tile");
 
 int consensus_partials(int64_t ld) { return (int)((ld + CD_COLS - 1) / CD_COLS); }
 
 __global__ void __launch_bounds__(CD_THREADS)
 consensus_partial_kernel(int M, int64_t D, int64_t ld, const float *__restrict__ X, double *__restrict__ partial)
 {
-    const int64_t j = ((int64_t)blockIdx.x * CD_THREADS + threadIdx.x) * 4;
+    const int64_t j = ((int64_t)blockIdx.x * CD_THREADS + threadIdx.x) * 4;   // CD_COLS divides TILE
     double acc = 0.0;
     if (j < D) {
-        const f32x4 x0 = load4(X + j);
+        const float *col = X + tiled_offset(M, 0, j);                          // worker i is i * TILE further
+        const f32x4 x0 = load4(col);
         double s[4] = {0, 0, 0, 0}, q[4] = {0, 0, 0, 0};
 #pragma unroll 4
         for (int i = 1; i < M; ++i) {
-            const f32x4 xi = load4(X + (size_t)i * ld + j);
+            const f32x4 xi = load4(col + (size_t)i * TILE);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const double d = (double)xi[e] - (double)x0[e];

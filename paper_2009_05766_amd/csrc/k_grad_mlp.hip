@@ -5,6 +5,7 @@
 // This file holds the general tiled kernels (any shape, fp32 FMA).  With bf16 operands the inputs of
 // every product are rounded to bfloat16 first and accumulated in fp32.
 #include "kernels.h"
+#include "layout.h"
 
 namespace netmax {
 
@@ -40,19 +41,19 @@ struct LayerInput {
 // Z = A W + b, optional ReLU.  rows = batch, cols = dout, K = din.
 struct FwdProblem {
     static constexpr bool A_K_FAST = true, B_C_FAST = true;
-    LayerInput in; const float *X; int64_t ld, woff, din, dout; int B, relu, round; float *out;
+    LayerInput in; const float *X; int64_t woff, din, dout; int M, B, relu, round; float *out;
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return din; }
     __device__ float a(int g, int64_t r, int64_t k) const { return in.at(g, (int)r, k); }
     __device__ float b(int g, int64_t k, int64_t c) const
     {
-        const float w = X[(size_t)g * ld + woff + k * dout + c];
+        const float w = X[tiled_offset(M, g, woff + k * dout + c)];
         return round ? round_bf16(w) : w;
     }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
-        float z = acc + X[(size_t)g * ld + woff + din * dout + c];
+        float z = acc + X[tiled_offset(M, g, woff + din * dout + c)];
         if (relu) z = z > 0.0f ? z : 0.0f;
         out[((size_t)g * B + r) * dout + c] = z;
     }
@@ -61,7 +62,7 @@ struct FwdProblem {
 // dA = (dZ W^T) * [A > 0].  rows = batch, cols = din, K = dout.
 struct DgradProblem {
     static constexpr bool A_K_FAST = true, B_C_FAST = false;
-    const float *dz; const float *X; const float *act; int64_t ld, woff, din, dout; int B, round; float *out;
+    const float *dz; const float *X; const float *act; int64_t woff, din, dout; int M, B, round; float *out;
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return din; }
     __device__ int64_t depth() const { return dout; }
@@ -72,7 +73,7 @@ struct DgradProblem {
     }
     __device__ float b(int g, int64_t k, int64_t c) const
     {
-        const float w = X[(size_t)g * ld + woff + c * dout + k];
+        const float w = X[tiled_offset(M, g, woff + c * dout + k)];
         return round ? round_bf16(w) : w;
     }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
@@ -85,7 +86,7 @@ struct DgradProblem {
 // dW = A^T dZ.  rows = din, cols = dout, K = batch.
 struct WgradProblem {
     static constexpr bool A_K_FAST = false, B_C_FAST = true;
-    LayerInput in; const float *dz; int64_t ld, woff, din, dout; int B, round; float *G;
+    LayerInput in; const float *dz; int64_t woff, din, dout; int M, B, round; float *G;
     __device__ int64_t rows() const { return din; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return B; }
@@ -97,7 +98,7 @@ struct WgradProblem {
     }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
-        G[(size_t)g * ld + woff + r * dout + c] = acc;
+        G[tiled_offset(M, g, woff + r * dout + c)] = acc;
     }
 };
 
@@ -187,10 +188,9 @@ softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const in
     if (b == 0) loss[g] = red[0] / (float)B;
 }
 
-// db = column sums of dZ; thread per (worker, output).  With zero_from >= 0 the threads also clear the
-// padding columns zero_from..ld-1 of the gradient row.
+// db = column sums of dZ; thread per (worker, output).
 __global__ void __launch_bounds__(256)
-bias_grad_kernel(int M, int B, int64_t dout, const float *__restrict__ dz, int64_t ld, int64_t boff,
+bias_grad_kernel(int M, int B, int64_t dout, const float *__restrict__ dz, int64_t boff,
                  float *__restrict__ G)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -199,7 +199,7 @@ bias_grad_kernel(int M, int B, int64_t dout, const float *__restrict__ dz, int64
     const int64_t c = t - (int64_t)g * dout;
     float s = 0.0f;
     for (int b = 0; b < B; ++b) s += dz[((size_t)g * B + b) * dout + c];
-    G[(size_t)g * ld + boff + c] = s;
+    G[tiled_offset(M, g, boff + c)] = s;
 }
 
 __global__ void __launch_bounds__(256) zero_padding_kernel(int M, int64_t D, int64_t ld, float *__restrict__ G)
@@ -208,7 +208,7 @@ __global__ void __launch_bounds__(256) zero_padding_kernel(int M, int64_t D, int
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= (int64_t)M * pad) return;
     const int g = (int)(t / pad);
-    G[(size_t)g * ld + D + (t - (int64_t)g * pad)] = 0.0f;
+    G[tiled_offset(M, g, D + (t - (int64_t)g * pad))] = 0.0f;
 }
 
 void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
@@ -224,7 +224,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
     // forward
     for (int l = 0; l < L; ++l) {
         FwdProblem f;
-        f.in = input_of(l); f.X = X; f.ld = p.ld; f.woff = p.woff[l]; f.din = p.dims[l]; f.dout = p.dims[l + 1];
+        f.in = input_of(l); f.X = X; f.M = p.M; f.woff = p.woff[l]; f.din = p.dims[l]; f.dout = p.dims[l + 1];
         f.B = p.B; f.relu = (l + 1 < L); f.round = p.bf16; f.out = p.act[l + 1];
         launch_gemm(s, f, p.M, p.B, f.dout);
     }
@@ -237,15 +237,15 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
     for (int l = L - 1; l >= 0; --l) {
         const int64_t din = p.dims[l], dout = p.dims[l + 1];
         WgradProblem wg;
-        wg.in = input_of(l); wg.dz = p.dz[cur]; wg.ld = p.ld; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
+        wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
         wg.B = p.B; wg.round = p.bf16; wg.G = G;
         launch_gemm(s, wg, p.M, din, dout);
         const int64_t nb = (int64_t)p.M * dout;
         hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, p.M, p.B, dout,
-                           p.dz[cur], p.ld, p.woff[l] + din * dout, G);
+                           p.dz[cur], p.woff[l] + din * dout, G);
         if (l > 0) {
             DgradProblem dg;
-            dg.dz = p.dz[cur]; dg.X = X; dg.act = p.act[l]; dg.ld = p.ld; dg.woff = p.woff[l]; dg.din = din;
+            dg.dz = p.dz[cur]; dg.X = X; dg.act = p.act[l]; dg.M = p.M; dg.woff = p.woff[l]; dg.din = din;
             dg.dout = dout; dg.B = p.B; dg.round = p.bf16; dg.out = p.dz[cur ^ 1];
             launch_gemm(s, dg, p.M, p.B, din);
             cur ^= 1;

@@ -1,4 +1,5 @@
 // Internal launch interface between the C ABI (netmax_api.hip) and the gfx950 kernels.
+// X, V, G are in the worker-interleaved tile layout of layout.h; ld is a multiple of TILE.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -26,6 +27,10 @@ void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float
 int consensus_partials(int64_t ld);
 void launch_consensus(hipStream_t s, int M, int64_t D, int64_t ld, const float *X, double *partial,
                       double *out_dev);
+
+// Layout conversion between row-major [M][row_ld] and the tile layout (columns >= cols read as / are left 0).
+void launch_pack(hipStream_t s, int M, int64_t cols, int64_t ld, const float *rows, int64_t row_ld, float *tiled);
+void launch_unpack(hipStream_t s, int M, int64_t cols, const float *tiled, float *rows, int64_t row_ld);
 
 // Per-worker MLP / softmax-regression gradient (grouped GEMMs).
 struct MlpPlan {

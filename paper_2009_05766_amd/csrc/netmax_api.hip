@@ -2,6 +2,7 @@
 // kernel launches.  Everything that touches model data runs in the kernels of this directory.
 #include "../../include/netmax.h"
 #include "kernels.h"
+#include "layout.h"
 
 #include <cmath>
 #include <cstdio>
@@ -184,9 +185,10 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
     if (!cfg || !cfg->P) return fail(nullptr, NETMAX_EINVAL, "cfg or cfg->P is NULL");
     char buf[200];
     if (cfg->M < 2 || cfg->M > 4096) return fail(nullptr, NETMAX_EINVAL, "M must be in 2..4096");
-    if (cfg->D < 1 || cfg->ld < cfg->D || cfg->ld % 64 != 0)
-        return fail(nullptr, NETMAX_EINVAL, "need 1 <= D <= ld and ld a multiple of 64");
-    if ((cfg->ld + 4095) / 4096 + 8 > (int64_t)0x7FFFFFFF / cfg->M)
+    static_assert(NETMAX_TILE == TILE, "the header and the kernels must agree on the tile size");
+    if (cfg->D < 1 || cfg->ld < cfg->D || cfg->ld % TILE != 0)
+        return fail(nullptr, NETMAX_EINVAL, "need 1 <= D <= ld and ld a multiple of NETMAX_TILE");
+    if ((int64_t)cfg->M * (cfg->ld / 4) / 256 + 8 > (int64_t)0x7FFFFFFF)
         return fail(nullptr, NETMAX_EINVAL, "M * ld is too large for one launch");
     if (!(cfg->lr > 0.0f) || !(cfg->momentum >= 0.0f) || !(cfg->momentum < 1.0f) || !(cfg->weight_decay >= 0.0f) ||
         !(cfg->rho >= 0.0f))
@@ -386,6 +388,22 @@ extern "C" int netmax_bind_data(netmax_ctx *ctx, const void *feats, const int32_
     ctx->labels = labels;
     ctx->data_bound = true;
     return NETMAX_OK;
+}
+
+extern "C" int netmax_pack(netmax_ctx *ctx, const float *rows_dev, int64_t row_ld, float *tiled_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!rows_dev || !tiled_dev || row_ld < ctx->cfg.D) return fail(ctx, NETMAX_EINVAL, "NULL pointer or row_ld < D");
+    launch_pack(ctx->stream, ctx->cfg.M, ctx->cfg.D, ctx->cfg.ld, rows_dev, row_ld, tiled_dev);
+    return check_launch(ctx, "pack");
+}
+
+extern "C" int netmax_unpack(netmax_ctx *ctx, const float *tiled_dev, float *rows_dev, int64_t row_ld)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!rows_dev || !tiled_dev || row_ld < ctx->cfg.D) return fail(ctx, NETMAX_EINVAL, "NULL pointer or row_ld < D");
+    launch_unpack(ctx->stream, ctx->cfg.M, ctx->cfg.D, tiled_dev, rows_dev, row_ld);
+    return check_launch(ctx, "unpack");
 }
 
 extern "C" int netmax_sample_peers(netmax_ctx *ctx, uint64_t iter, int32_t *peers_dev)

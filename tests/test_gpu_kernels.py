@@ -79,14 +79,14 @@ def test_batch_indices_bit_exact(ora, M, B, n):
     gpu.close()
 
 
-@pytest.mark.parametrize("M,D", [(3, 64), (4, 4096 * 3 + 64 * 5 - 3), (2, 1), (7, 70001)])
+@pytest.mark.parametrize("M,D", [(3, 64), (4, 2048 * 3 + 64 * 5 - 3), (2, 1), (7, 70001)])
 def test_synthetic_gradient(ora, M, D):
     w = workload("cfg3", M=M, D=D)
     inp = inputs_of(w)
     gpu = make_gpu(w, inp)
     for it in (0, 3):
         gpu.local_step(it)
-        got = gpu.g.cpu().numpy()
+        got = gpu.get("g").cpu().numpy()
         want = ora.synth_grad(M, w.D, w.ld, float(np.float32(w.grad_sigma)), w.seed, it)
         assert np.all(got[:, D:] == 0)
         # single-precision log / sqrt / sincos against double: a few ulp of |g| and of sigma near zeros of cos/sin
@@ -95,8 +95,8 @@ def test_synthetic_gradient(ora, M, D):
     gpu.close()
 
 
-@pytest.mark.parametrize("M,D,mu,wd", [(8, 4096 * 3 + 64 * 5, 0.9, 0.0), (5, 100, 0.0, 0.0), (16, 33000, 0.9, 1e-4),
-                                        (2, 4096, 0.5, 0.0)])
+@pytest.mark.parametrize("M,D,mu,wd", [(8, 2048 * 3 + 64 * 5, 0.9, 0.0), (5, 100, 0.0, 0.0), (16, 33000, 0.9, 1e-4),
+                                        (2, 4096, 0.5, 0.0), (64, 2048 * 17, 0.9, 0.0)])
 def test_mix_one_step(ora, M, D, mu, wd):
     w = workload("cfg3", M=M, D=D)
     inp = inputs_of(w)
@@ -105,22 +105,24 @@ def test_mix_one_step(ora, M, D, mu, wd):
     rng = np.random.default_rng(M)
     V0 = (0.05 * rng.standard_normal((M, w.ld))).astype(np.float32)
     V0[:, D:] = 0
-    gpu.v.copy_(torch.from_numpy(V0))
+    gpu.set("v", V0)
     o.V[:] = V0
     for it in range(3):
         peer = o.sample_peers(it)
         if it == 1:
             peer[0] = 0                              # a self draw: local step only
         o.local_step(it)
-        gpu.g.copy_(torch.from_numpy(o.G))           # identical gradients: isolates the mix kernel
+        gpu.set("g", o.G)                          # identical gradients: isolates the mix kernel
         gpu.peers.copy_(torch.from_numpy(peer))
         gpu.mix(it)
         o.mix(peer)
-        X = gpu.params().cpu().numpy()
+        X = gpu.get("x").cpu().numpy()
         assert rel_err_rows(X, o.X) < 1e-6
-        assert rel_err_rows(gpu.v.cpu().numpy(), o.V) < 1e-6
+        assert rel_err_rows(gpu.get("v").cpu().numpy(), o.V) < 1e-6
         assert np.all(X[:, D:] == 0)
-        np.testing.assert_allclose(X, o.X, rtol=0, atol=2e-7 * np.abs(o.X).max())
+        # element by element: at most a few single-precision roundings (three fused multiply-adds and two
+        # subtractions) at the magnitude of the largest parameter
+        np.testing.assert_allclose(X, o.X, rtol=0, atol=4 * 2.0**-23 * np.abs(o.X).max())
     assert nm.netmax_iteration(gpu.ctx) == 3
     gpu.close()
 
@@ -132,11 +134,11 @@ def test_mix_identical_copies_fixed_point_and_out_of_range_peer():
     gpu = make_gpu(w, dict(inp, X0=X0), grad_sigma=0.0)
     for it in range(5):
         gpu.step(it)
-        assert np.array_equal(gpu.params().cpu().numpy(), X0)
+        assert np.array_equal(gpu.get("x").cpu().numpy(), X0)
     assert gpu.consensus_dist() == 0.0
     gpu.peers.fill_(-7)                               # treated as self draws
     gpu.mix(5)
-    assert np.array_equal(gpu.params().cpu().numpy(), X0)
+    assert np.array_equal(gpu.get("x").cpu().numpy(), X0)
     gpu.close()
 
 
@@ -150,7 +152,7 @@ def test_consensus_distance(ora, M, D):
     # a large common offset must not hurt (no cancellation): shift every copy by the same vector
     X = inp["X0"] + np.float32(100.0)
     X[:, D:] = 0
-    gpu.params().copy_(torch.from_numpy(X))
+    gpu.set("x", X)
     assert gpu.consensus_dist() == pytest.approx(ora.consensus_dist(X, D), rel=1e-9)
     gpu.close()
 
@@ -185,7 +187,7 @@ def test_local_gradient(ora, name, over):
     for it in (0, 5):
         gpu.local_step(it)
         o.local_step(it)
-        G = gpu.g.cpu().numpy()
+        G = gpu.get("g").cpu().numpy()
         assert np.all(G[:, w.D:] == 0)
         err = rel_err_rows(G, o.G)
         assert err < (TOL_GRAD_BF16_SAME_OPERANDS if bf16 else TOL_GRAD_F32), err
@@ -201,11 +203,11 @@ def test_error_paths():
     w = workload("cfg1", M=3, n_per_worker=8, dims=(4, 3), batch=2)
     inp = inputs_of(w)
     with pytest.raises(nm.NetmaxError) as e:
-        nm.netmax_init(M=3, D=14, ld=64, model=nm.NETMAX_MLP, dims=(4, 3), batch=2, lr=0.1, rho=0.1, seed=1, P=inp["P"])
+        nm.netmax_init(M=3, D=14, ld=2048, model=nm.NETMAX_MLP, dims=(4, 3), batch=2, lr=0.1, rho=0.1, seed=1, P=inp["P"])
     assert e.value.code == nm.NETMAX_EINVAL and "15" in str(e.value)
     with pytest.raises(nm.NetmaxError):
-        nm.netmax_init(M=3, D=15, ld=60, model=nm.NETMAX_MLP, dims=(4, 3), batch=2, lr=0.1, rho=0.1, seed=1, P=inp["P"])
-    ctx = nm.netmax_init(M=3, D=15, ld=64, model=nm.NETMAX_MLP, dims=(4, 3), batch=2, lr=0.1, rho=0.1, seed=1, P=inp["P"])
+        nm.netmax_init(M=3, D=15, ld=2000, model=nm.NETMAX_MLP, dims=(4, 3), batch=2, lr=0.1, rho=0.1, seed=1, P=inp["P"])
+    ctx = nm.netmax_init(M=3, D=15, ld=2048, model=nm.NETMAX_MLP, dims=(4, 3), batch=2, lr=0.1, rho=0.1, seed=1, P=inp["P"])
     with pytest.raises(nm.NetmaxError) as e:
         nm.netmax_local_step(ctx, 0)
     assert e.value.code == nm.NETMAX_ESTATE

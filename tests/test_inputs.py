@@ -9,12 +9,12 @@ from netmax_inputs import (workload, policy_for, make_shards, init_params, WORKL
 def test_parameter_counts():
     assert workload("cfg1").D == 2570
     assert workload("cfg2").D == 407050
-    assert workload("cfg3").D == 11_200_000 and workload("cfg3").ld == 11_200_000
+    assert workload("cfg3").D == 11_200_000 and workload("cfg3").ld == 11_200_512
     assert workload("cfg4").D == 20_000_000
     assert workload("cfg5").D == 4_206_602
     for n in WORKLOAD_NAMES:
         w = workload(n)
-        assert w.ld % 64 == 0 and w.ld >= w.D
+        assert w.ld % 2048 == 0 and w.ld - 2048 < w.D <= w.ld
 
 
 @pytest.mark.parametrize("name", WORKLOAD_NAMES)
