@@ -24,6 +24,18 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # its own, so the minimum HBM traffic counts x once: 5 * 4 = 20 B.  (Counting the peer read too gives 24 B.)
 MIX_BYTES_MIN, MIX_BYTES_NAIVE = 20, 24
 
+# HBM bytes per mix launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/mix_kernel_<workload>.md), each
+# counter scaled by what it reads for a plain device copy of known size.  Valid only for the kernel sources they
+# were taken with: keyed by the sha256 prefix of k_mix.hip + layout.h + vec.h, reported as null otherwise.
+MEASURED_TRAFFIC = {"cfg3": {"sources": "23936c2060ea38f1.3f97687d5424e9a2.f872db49a5d92e6f", "bytes": 14337775863}}
+
+
+def mix_sources_digest() -> str:
+    import hashlib
+    d = os.path.join(ROOT, "paper_2009_05766_amd", "csrc")
+    return ".".join(hashlib.sha256(open(os.path.join(d, f), "rb").read()).hexdigest()[:16]
+                    for f in ("k_mix.hip", "layout.h", "vec.h"))
+
 
 def describe(w) -> str:
     if w.model == "flat":
@@ -134,8 +146,10 @@ def main() -> int:
     elems = w.M * w.ld
     mix_s = ms_mix * 1e-3
     achieved = MIX_BYTES_MIN * elems / mix_s / 1e9
+    rec = MEASURED_TRAFFIC.get(w.name)
+    traffic = rec["bytes"] if rec and rec["sources"] == mix_sources_digest() else None
     roofline = {"bound": "hbm", "kernel": "mix_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "bytes_per_worker_param": MIX_BYTES_MIN, "avg_launch_ms": float(ms_mix),
                 "achieved_counting_peer_read": MIX_BYTES_NAIVE * elems / mix_s / 1e9}
 
