@@ -1,0 +1,393 @@
+// Grouped GEMMs of the perceptron gradient on the CDNA4 matrix cores, bf16 operands / fp32 accumulate.
+// One group per worker (its own batch times its own weights), so every weight is used by only `batch`
+// rows: the kernels are bound by streaming the fp32 master weights from HBM and the gradient back, and
+// are organised around that (128-bit loads along the weights' contiguous dimension, conversion to
+// bfloat16 on the way into LDS), with v_mfma_f32_32x32x16_bf16 doing the arithmetic.
+//
+// Lane layout of v_mfma_f32_32x32x16_bf16 (64 lanes, l = lane):
+//   A operand: 8 values A[row = l % 32][k = 8 (l / 32) + 0..7]
+//   B operand: 8 values B[k = 8 (l / 32) + 0..7][col = l % 32]
+//   D:        16 values D[row = 4 (l / 32) + v % 4 + 8 (v / 4)][col = l % 32], v = 0..15
+#include "bf16.h"
+#include "kernels.h"
+#include "layout.h"
+
+namespace netmax {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int MF_THREADS = 256;      // 4 waves, arranged 2 x 2 over a 128 x 128 output tile
+constexpr int MF_BM = 128, MF_BN = 128, MF_BK = 32;
+constexpr int MF_PITCH = MF_BK + 8;  // LDS row pitch in bf16 elements (80 B: 16-byte aligned, conflict-free b128 reads)
+
+__device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 acc)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ int d_row(int lane, int v) { return 4 * (lane >> 5) + (v & 3) + 8 * (v >> 2); }
+
+// One K step of the 128 x 128 tile from LDS: As[m][k], Bs[n][k], both k-contiguous.
+__device__ __forceinline__ void tile_mma(const uint16_t (*As)[MF_PITCH], const uint16_t (*Bs)[MF_PITCH], int wm, int wn,
+                                         int lane, f32x16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int ks = 0; ks < MF_BK / 16; ++ks) {
+        const int kofs = 16 * ks + 8 * (lane >> 5);
+        u32x4 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const u32x4 *>(&As[64 * wm + 32 * i + (lane & 31)][kofs]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&Bs[64 * wn + 32 * j + (lane & 31)][kofs]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Forward: H = relu(A W + b) for one worker and one block of 128 output columns; all batch rows.
+// A: gathered bf16 data rows (first layer) or the previous layer's bf16 activations [B][din].
+// W: fp32 master weights [din][dout] inside the worker's parameter row (tile layout), read with 128-bit
+// loads along dout, transposed 4 x 4 in registers and stored to LDS as bf16 [n][k].
+// Output: bf16 activations, row-major [B][dout] and transposed [dout][B].
+struct FwdMfmaArgs {
+    const uint16_t *feats; const int64_t *row0; const int32_t *idx;   // first layer
+    const uint16_t *a_prev;                                           // later layers: [M][B][din]
+    const float *X; int64_t woff; int M, B; int64_t din, dout; int relu;
+    uint16_t *out, *out_t;
+};
+
+template <bool FIRST>
+__global__ void __launch_bounds__(MF_THREADS) fwd_mfma_kernel(FwdMfmaArgs p)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t As[MF_BM][MF_PITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[MF_BN][MF_PITCH];
+    const int g = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int64_t n0 = (int64_t)blockIdx.x * MF_BN;
+
+    // A: two 16-byte chunks per thread: rows ar[c], k offset 8 * (chunk % 4)
+    const uint16_t *a_src[2];
+    int a_row[2], a_k[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int chunk = t + c * MF_THREADS;
+        a_row[c] = chunk >> 2;
+        a_k[c] = (chunk & 3) * 8;
+        if (a_row[c] < p.B) {
+            const int64_t row = FIRST ? p.row0[g] + p.idx[(size_t)g * p.B + a_row[c]] : (int64_t)g * p.B + a_row[c];
+            a_src[c] = (FIRST ? p.feats : p.a_prev) + row * p.din + a_k[c];
+        } else {
+            a_src[c] = nullptr;
+        }
+    }
+    // W: a 4 (k) x 4 (n) block per thread
+    const int kg = t >> 5, nq = t & 31;
+    const int64_t w_col = p.woff + n0 + 4 * nq;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    u32x4 ra[2];
+    f32x4_t rw[4];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            ra[c] = a_src[c] ? *reinterpret_cast<const u32x4 *>(a_src[c] + k0) : (u32x4){0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            rw[r] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, w_col + (k0 + 4 * kg + r) * p.dout));
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4 *>(&As[a_row[c]][a_k[c]]) = ra[c];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {   // column n = 4 nq + e gets its four consecutive k
+            u32x2 packed;
+            packed.x = pack_bf16x2(rw[0][e], rw[1][e]);
+            packed.y = pack_bf16x2(rw[2][e], rw[3][e]);
+            *reinterpret_cast<u32x2 *>(&Bs[4 * nq + e][4 * kg]) = packed;
+        }
+    };
+
+    fetch(0);
+    for (int64_t k0 = 0; k0 < p.din; k0 += MF_BK) {
+        __syncthreads();            // the previous step's reads of LDS are done
+        stash();
+        __syncthreads();
+        if (k0 + MF_BK < p.din) fetch(k0 + MF_BK);   // overlaps with the matrix instructions below
+        tile_mma(As, Bs, wm, wn, lane, acc);
+    }
+
+    // epilogue: bias, ReLU, bf16, both layouts
+    const float *bias = p.X;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t col = n0 + 64 * wn + 32 * j + (lane & 31);
+        const float bcol = bias[tiled_offset(p.M, g, p.woff + p.din * p.dout + col)];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {           // four groups of four consecutive rows
+                const int row = 64 * wm + 32 * i + d_row(lane, 4 * q);
+                float z[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    z[e] = acc[i][j][4 * q + e] + bcol;
+                    if (p.relu) z[e] = z[e] > 0.0f ? z[e] : 0.0f;
+                }
+                if (row + 3 < p.B) {
+                    u32x2 packed;
+                    packed.x = pack_bf16x2(z[0], z[1]);
+                    packed.y = pack_bf16x2(z[2], z[3]);
+                    *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.dout + col) * p.B + row) = packed;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) p.out[((size_t)g * p.B + row + e) * p.dout + col] = (uint16_t)bf16_bits(z[e]);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Backward through a layer: dA = (dZ W^T) * [A > 0] for one worker and 128 input features (output columns).
+// dZ: bf16 [B][dout]; W rows are contiguous along the contraction index, so they go to LDS untransposed.
+// Output: fp32 [B][din] (for the bias gradient), bf16 [B][din] and bf16 transposed [din][B].
+struct DgradMfmaArgs {
+    const uint16_t *dz; const float *X; int64_t woff; int M, B; int64_t din, dout;
+    const uint16_t *act;          // bf16 activations of this layer's input [M][B][din] (ReLU mask)
+    float *out_f32; uint16_t *out, *out_t;
+};
+
+__global__ void __launch_bounds__(MF_THREADS) dgrad_mfma_kernel(DgradMfmaArgs p)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t As[MF_BM][MF_PITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[MF_BN][MF_PITCH];
+    const int g = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int64_t c0 = (int64_t)blockIdx.x * MF_BN;       // first input feature (output column) of this block
+
+    const uint16_t *a_src[2];
+    int a_row[2], a_k[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int chunk = t + c * MF_THREADS;
+        a_row[c] = chunk >> 2;
+        a_k[c] = (chunk & 3) * 8;
+        a_src[c] = a_row[c] < p.B ? p.dz + ((size_t)g * p.B + a_row[c]) * p.dout + a_k[c] : nullptr;
+    }
+    // W: four 128-bit loads per thread, chunk = t + 256 r: feature row = chunk / 8, quad = chunk % 8
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    u32x4 ra[2];
+    f32x4_t rw[4];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            ra[c] = a_src[c] ? *reinterpret_cast<const u32x4 *>(a_src[c] + k0) : (u32x4){0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int chunk = t + r * MF_THREADS;
+            const int64_t feat = c0 + (chunk >> 3);
+            rw[r] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, p.woff + feat * p.dout + k0 + 4 * (chunk & 7)));
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4 *>(&As[a_row[c]][a_k[c]]) = ra[c];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int chunk = t + r * MF_THREADS;
+            u32x2 packed;
+            packed.x = pack_bf16x2(rw[r][0], rw[r][1]);
+            packed.y = pack_bf16x2(rw[r][2], rw[r][3]);
+            *reinterpret_cast<u32x2 *>(&Bs[chunk >> 3][4 * (chunk & 7)]) = packed;
+        }
+    };
+
+    fetch(0);
+    for (int64_t k0 = 0; k0 < p.dout; k0 += MF_BK) {
+        __syncthreads();
+        stash();
+        __syncthreads();
+        if (k0 + MF_BK < p.dout) fetch(k0 + MF_BK);
+        tile_mma(As, Bs, wm, wn, lane, acc);
+    }
+
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t col = c0 + 64 * wn + 32 * j + (lane & 31);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = 64 * wm + 32 * i + d_row(lane, 4 * q);
+                if (row + 3 < p.B) {
+                    float d[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const size_t at = ((size_t)g * p.B + row + e) * p.din + col;
+                        d[e] = bf16_positive(p.act[at]) ? acc[i][j][4 * q + e] : 0.0f;
+                        p.out_f32[at] = d[e];
+                        p.out[at] = (uint16_t)bf16_bits(d[e]);
+                    }
+                    u32x2 packed;
+                    packed.x = pack_bf16x2(d[0], d[1]);
+                    packed.y = pack_bf16x2(d[2], d[3]);
+                    *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.din + col) * p.B + row) = packed;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Weight gradient: dW = A^T dZ for one worker and one 128 x 128 block of W.  The contraction runs over
+// the batch (<= 128), so both operands are small: each lane reads its matrix-instruction operands
+// straight from the transposed bf16 copies A^T [din][B] and dZ^T [dout][B] (batch-contiguous, L2
+// resident); the product is written once, fp32, into the gradient row (tile layout).
+struct WgradMfmaArgs {
+    const uint16_t *a_t, *dz_t; int M, B; int64_t din, dout, woff; float *G;
+};
+
+__global__ void __launch_bounds__(MF_THREADS) wgrad_mfma_kernel(WgradMfmaArgs p)
+{
+    const int g = blockIdx.z, t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int64_t r0 = (int64_t)blockIdx.y * MF_BM + 64 * wm, n0 = (int64_t)blockIdx.x * MF_BN + 64 * wn;
+    const uint16_t *a_ptr[2], *b_ptr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a_ptr[i] = p.a_t + ((size_t)g * p.din + r0 + 32 * i + (lane & 31)) * p.B + 8 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b_ptr[j] = p.dz_t + ((size_t)g * p.dout + n0 + 32 * j + (lane & 31)) * p.B + 8 * (lane >> 5);
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    for (int b0 = 0; b0 < p.B; b0 += 16) {
+        u32x4 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const u32x4 *>(a_ptr[i] + b0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(b_ptr[j] + b0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
+    }
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t col = n0 + 32 * j + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t row = r0 + 32 * i + d_row(lane, v);
+                __builtin_nontemporal_store(acc[i][j][v], p.G + tiled_offset(p.M, g, p.woff + row * p.dout + col));
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Transposed bf16 copy of each worker's gathered batch: out[g][k][b] = feats[row0[g] + idx[g][b]][k].
+// One workgroup = one worker x 64 features; the tile is turned in LDS.
+__global__ void __launch_bounds__(256)
+gather_transpose_kernel(const uint16_t *__restrict__ feats, const int64_t *__restrict__ row0,
+                        const int32_t *__restrict__ idx, int B, int64_t din, uint16_t *__restrict__ out)
+{
+    __shared__ uint16_t tile[128][66];      // [b][k], pitch 33 words: conflict-free column reads
+    const int g = blockIdx.y, t = threadIdx.x;
+    const int64_t k0 = (int64_t)blockIdx.x * 64;
+    {
+        const int b = t >> 1, half = t & 1;
+        if (b < B) {
+            const uint16_t *src = feats + (row0[g] + idx[(size_t)g * B + b]) * din + k0 + 32 * half;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(src + 8 * c);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) *reinterpret_cast<uint32_t *>(&tile[b][32 * half + 8 * c + 2 * e]) = v[e];
+            }
+        }
+    }
+    __syncthreads();
+    {
+        const int k = t >> 2, bq = t & 3;       // 32 batch entries per thread
+        if (32 * bq < B) {
+            uint16_t *dst = out + ((size_t)g * din + k0 + k) * B + 32 * bq;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                u32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int b = 32 * bq + 8 * c + 2 * e;
+                    v[e] = (uint32_t)tile[b][k] | ((uint32_t)tile[b + 1][k] << 16);
+                }
+                *reinterpret_cast<u32x4 *>(dst + 8 * c) = v;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+bool mfma_layer_ok(const MlpPlan &p, int l)
+{
+    const int64_t din = p.dims[l], dout = p.dims[l + 1];
+    return p.bf16 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && dout % 128 == 0 && p.woff[l] % 4 == 0;
+}
+
+void launch_gather_transpose(hipStream_t s, const MlpPlan &p)
+{
+    hipLaunchKernelGGL(gather_transpose_kernel, dim3((unsigned)(p.dims[0] / 64), p.M), dim3(256), 0, s,
+                       (const uint16_t *)p.feats, p.row0, p.idx, p.B, p.dims[0], p.ht[0]);
+}
+
+void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X)
+{
+    FwdMfmaArgs a;
+    a.feats = (const uint16_t *)p.feats; a.row0 = p.row0; a.idx = p.idx; a.a_prev = l > 0 ? p.hb[l] : nullptr;
+    a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
+    a.relu = (l + 1 < p.n_layers); a.out = p.hb[l + 1]; a.out_t = p.ht[l + 1];
+    const dim3 grid((unsigned)(a.dout / MF_BN), p.M);
+    if (l == 0) hipLaunchKernelGGL(fwd_mfma_kernel<true>, grid, dim3(MF_THREADS), 0, s, a);
+    else hipLaunchKernelGGL(fwd_mfma_kernel<false>, grid, dim3(MF_THREADS), 0, s, a);
+}
+
+void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, int cur)
+{
+    DgradMfmaArgs a;
+    a.dz = p.dzb[cur]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
+    a.act = p.hb[l]; a.out_f32 = p.dz[cur ^ 1]; a.out = p.dzb[cur ^ 1]; a.out_t = p.dzt[cur ^ 1];
+    hipLaunchKernelGGL(dgrad_mfma_kernel, dim3((unsigned)(a.din / MF_BN), p.M), dim3(MF_THREADS), 0, s, a);
+}
+
+void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur)
+{
+    WgradMfmaArgs a;
+    a.a_t = p.ht[l]; a.dz_t = p.dzt[cur]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
+    a.woff = p.woff[l]; a.G = G;
+    hipLaunchKernelGGL(wgrad_mfma_kernel, dim3((unsigned)(a.dout / MF_BN), (unsigned)(a.din / MF_BM), p.M),
+                       dim3(MF_THREADS), 0, s, a);
+}
+
+}  // namespace netmax

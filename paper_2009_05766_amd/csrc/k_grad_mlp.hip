@@ -4,6 +4,7 @@
 //
 // This file holds the general tiled kernels (any shape, fp32 FMA).  With bf16 operands the inputs of
 // every product are rounded to bfloat16 first and accumulated in fp32.
+#include "bf16.h"
 #include "kernels.h"
 #include "layout.h"
 
@@ -11,19 +12,11 @@ namespace netmax {
 
 constexpr int TM = 64, TN = 64, TK = 16, GEMM_THREADS = 256;
 
-__device__ __forceinline__ float round_bf16(float x)
-{
-    uint32_t b = __float_as_uint(x);
-    b += 0x7FFFu + ((b >> 16) & 1u);     // nearest even
-    return __uint_as_float(b & 0xFFFF0000u);
-}
-
-__device__ __forceinline__ float bf16_bits_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
-
 // Input of layer l for worker g, batch row r, feature k: the gathered data row for l = 0, else the
-// previous layer's activation.
+// previous layer's activation (fp32, or its stored bfloat16 copy when the operands are bf16).
 struct LayerInput {
     const void *feats; int feats_bf16; const int64_t *row0; const int32_t *idx; const float *act_prev;
+    const uint16_t *act_prev_bf16;
     int B; int64_t din; int first; int round;
     __device__ __forceinline__ float at(int g, int r, int64_t k) const
     {
@@ -33,6 +26,7 @@ struct LayerInput {
                               : (round ? round_bf16(((const float *)feats)[row * din + k])
                                        : ((const float *)feats)[row * din + k]);
         }
+        if (act_prev_bf16) return bf16_bits_to_float(act_prev_bf16[((size_t)g * B + r) * din + k]);
         const float a = act_prev[((size_t)g * B + r) * din + k];
         return round ? round_bf16(a) : a;
     }
@@ -42,6 +36,7 @@ struct LayerInput {
 struct FwdProblem {
     static constexpr bool A_K_FAST = true, B_C_FAST = true;
     LayerInput in; const float *X; int64_t woff, din, dout; int M, B, relu, round; float *out;
+    uint16_t *out_bf16, *out_bf16_t;     // optional bfloat16 copies: [B][dout] and transposed [dout][B]
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return din; }
@@ -55,14 +50,20 @@ struct FwdProblem {
     {
         float z = acc + X[tiled_offset(M, g, woff + din * dout + c)];
         if (relu) z = z > 0.0f ? z : 0.0f;
-        out[((size_t)g * B + r) * dout + c] = z;
+        if (out) out[((size_t)g * B + r) * dout + c] = z;
+        if (out_bf16) {
+            const uint16_t h = (uint16_t)bf16_bits(z);
+            out_bf16[((size_t)g * B + r) * dout + c] = h;
+            out_bf16_t[((size_t)g * dout + c) * B + r] = h;
+        }
     }
 };
 
 // dA = (dZ W^T) * [A > 0].  rows = batch, cols = din, K = dout.
 struct DgradProblem {
     static constexpr bool A_K_FAST = true, B_C_FAST = false;
-    const float *dz; const float *X; const float *act; int64_t woff, din, dout; int M, B, round; float *out;
+    const float *dz; const float *X; const float *act; const uint16_t *act_bf16; int64_t woff, din, dout;
+    int M, B, round; float *out; uint16_t *out_bf16, *out_bf16_t;
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return din; }
     __device__ int64_t depth() const { return dout; }
@@ -79,7 +80,14 @@ struct DgradProblem {
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
         const size_t q = ((size_t)g * B + r) * din + c;
-        out[q] = act[q] > 0.0f ? acc : 0.0f;
+        const bool on = act_bf16 ? bf16_positive(act_bf16[q]) : act[q] > 0.0f;
+        const float d = on ? acc : 0.0f;
+        out[q] = d;
+        if (out_bf16) {
+            const uint16_t h = (uint16_t)bf16_bits(d);
+            out_bf16[q] = h;
+            out_bf16_t[((size_t)g * din + c) * B + r] = h;
+        }
     }
 };
 
@@ -162,7 +170,7 @@ static void launch_gemm(hipStream_t s, const Problem &p, int groups, int64_t row
 __global__ void __launch_bounds__(1024)
 softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const int32_t *__restrict__ labels,
                     const int64_t *__restrict__ row0, const int32_t *__restrict__ idx, float *__restrict__ dz,
-                    float *__restrict__ loss)
+                    uint16_t *__restrict__ dz_bf16, uint16_t *__restrict__ dz_bf16_t, float *__restrict__ loss)
 {
     __shared__ float red[1024];
     const int g = blockIdx.x, b = threadIdx.x;
@@ -177,7 +185,15 @@ softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const in
         const int y = labels[row0[g] + idx[(size_t)g * B + b]];
         l = logf(sum) - (z[y] - mx);
         const float inv = 1.0f / sum, invB = 1.0f / (float)B;
-        for (int64_t o = 0; o < C; ++o) d[o] = (expf(z[o] - mx) * inv - (o == y ? 1.0f : 0.0f)) * invB;
+        for (int64_t o = 0; o < C; ++o) {
+            const float v = (expf(z[o] - mx) * inv - (o == y ? 1.0f : 0.0f)) * invB;
+            d[o] = v;
+            if (dz_bf16) {
+                const uint16_t h = (uint16_t)bf16_bits(v);
+                dz_bf16[((size_t)g * B + b) * C + o] = h;
+                dz_bf16_t[((size_t)g * C + o) * B + b] = h;
+            }
+        }
     }
     red[b] = l;
     __syncthreads();
@@ -214,40 +230,64 @@ __global__ void __launch_bounds__(256) zero_padding_kernel(int M, int64_t D, int
 void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
 {
     const int L = p.n_layers;
+    const bool bf = p.bf16 != 0;
+    bool fast[8] = {};
+    for (int l = 0; l < L; ++l) fast[l] = mfma_layer_ok(p, l);
     auto input_of = [&](int l) {
         LayerInput in;
         in.feats = p.feats; in.feats_bf16 = p.bf16; in.row0 = p.row0; in.idx = p.idx;
-        in.act_prev = l > 0 ? p.act[l] : nullptr;
+        in.act_prev = (l > 0 && !bf) ? p.act[l] : nullptr;
+        in.act_prev_bf16 = (l > 0 && bf) ? p.hb[l] : nullptr;
         in.B = p.B; in.din = p.dims[l]; in.first = (l == 0); in.round = p.bf16;
         return in;
     };
-    // forward
+    if (fast[0]) launch_gather_transpose(s, p);
+    // forward.  With bf16 operands the hidden activations are kept as bfloat16 only (both orientations).
     for (int l = 0; l < L; ++l) {
+        const bool last = (l + 1 == L);
+        if (fast[l] && !last) {
+            launch_fwd_mfma(s, p, l, X);
+            continue;
+        }
         FwdProblem f;
         f.in = input_of(l); f.X = X; f.M = p.M; f.woff = p.woff[l]; f.din = p.dims[l]; f.dout = p.dims[l + 1];
-        f.B = p.B; f.relu = (l + 1 < L); f.round = p.bf16; f.out = p.act[l + 1];
+        f.B = p.B; f.relu = !last; f.round = p.bf16;
+        f.out = (last || !bf) ? p.act[l + 1] : nullptr;
+        f.out_bf16 = (bf && !last) ? p.hb[l + 1] : nullptr;
+        f.out_bf16_t = (bf && !last) ? p.ht[l + 1] : nullptr;
         launch_gemm(s, f, p.M, p.B, f.dout);
     }
     // loss and dZ of the last layer
     const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
     hipLaunchKernelGGL(softmax_xent_kernel, dim3(p.M), dim3(sm_threads), 0, s, p.B, p.dims[L], p.act[L], p.labels,
-                       p.row0, p.idx, p.dz[0], p.loss);
+                       p.row0, p.idx, p.dz[0], bf ? p.dzb[0] : nullptr, bf ? p.dzt[0] : nullptr, p.loss);
     // backward
     int cur = 0;
     for (int l = L - 1; l >= 0; --l) {
         const int64_t din = p.dims[l], dout = p.dims[l + 1];
-        WgradProblem wg;
-        wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
-        wg.B = p.B; wg.round = p.bf16; wg.G = G;
-        launch_gemm(s, wg, p.M, din, dout);
+        if (fast[l]) {
+            launch_wgrad_mfma(s, p, l, G, cur);
+        } else {
+            WgradProblem wg;
+            wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
+            wg.B = p.B; wg.round = p.bf16; wg.G = G;
+            launch_gemm(s, wg, p.M, din, dout);
+        }
         const int64_t nb = (int64_t)p.M * dout;
         hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, p.M, p.B, dout,
                            p.dz[cur], p.woff[l] + din * dout, G);
         if (l > 0) {
-            DgradProblem dg;
-            dg.dz = p.dz[cur]; dg.X = X; dg.act = p.act[l]; dg.M = p.M; dg.woff = p.woff[l]; dg.din = din;
-            dg.dout = dout; dg.B = p.B; dg.round = p.bf16; dg.out = p.dz[cur ^ 1];
-            launch_gemm(s, dg, p.M, p.B, din);
+            if (fast[l]) {
+                launch_dgrad_mfma(s, p, l, X, cur);
+            } else {
+                DgradProblem dg;
+                dg.dz = p.dz[cur]; dg.X = X; dg.act = bf ? nullptr : p.act[l]; dg.act_bf16 = bf ? p.hb[l] : nullptr;
+                dg.M = p.M; dg.woff = p.woff[l]; dg.din = din; dg.dout = dout; dg.B = p.B; dg.round = p.bf16;
+                dg.out = p.dz[cur ^ 1];
+                dg.out_bf16 = bf ? p.dzb[cur ^ 1] : nullptr;
+                dg.out_bf16_t = bf ? p.dzt[cur ^ 1] : nullptr;
+                launch_gemm(s, dg, p.M, p.B, din);
+            }
             cur ^= 1;
         }
     }

@@ -46,7 +46,19 @@ struct MlpPlan {
     float *act[8];          // act[l], l = 1..n_layers: [M][B][dims[l]] post-activation (logits for the last)
     float *dz[2];           // two ping-pong buffers [M][B][max width]
     float *loss;            // [M]
+    // bf16 operands only: bfloat16 copies of activations and back-propagated errors, in both orientations
+    uint16_t *hb[8];        // hb[l], l = 1..n_layers-1: [M][B][dims[l]]
+    uint16_t *ht[8];        // ht[l], l = 0..n_layers-1: [M][dims[l]][B] (ht[0] = the gathered batch, transposed)
+    uint16_t *dzb[2];       // [M][B][max width]
+    uint16_t *dzt[2];       // [M][max width][B]
 };
 void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G);
+
+// Matrix-core kernels (k_grad_mfma.hip) for layers that mfma_layer_ok() accepts.
+bool mfma_layer_ok(const MlpPlan &p, int l);
+void launch_gather_transpose(hipStream_t s, const MlpPlan &p);
+void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X);
+void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, int cur);
+void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur);
 
 }  // namespace netmax

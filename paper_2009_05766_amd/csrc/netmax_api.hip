@@ -40,6 +40,9 @@ struct netmax_ctx {
     float *d_dz[2] = {};
     float *d_loss = nullptr;
     int32_t *d_flag = nullptr;
+    uint16_t *d_hb[NETMAX_MAX_LAYERS + 1] = {};
+    uint16_t *d_ht[NETMAX_MAX_LAYERS + 1] = {};
+    uint16_t *d_dzb[2] = {}, *d_dzt[2] = {};
     int64_t woff[NETMAX_MAX_LAYERS + 1] = {};
     // consensus distance
     double *d_partial = nullptr, *d_cd = nullptr;
@@ -166,6 +169,10 @@ static void release(netmax_ctx *ctx)
     for (auto *p : ctx->d_act) (void)hipFree(p);
     (void)hipFree(ctx->d_dz[0]); (void)hipFree(ctx->d_dz[1]);
     (void)hipFree(ctx->d_loss); (void)hipFree(ctx->d_flag);
+    for (auto *p : ctx->d_hb) (void)hipFree(p);
+    for (auto *p : ctx->d_ht) (void)hipFree(p);
+    for (auto *p : ctx->d_dzb) (void)hipFree(p);
+    for (auto *p : ctx->d_dzt) (void)hipFree(p);
     (void)hipFree(ctx->d_partial); (void)hipFree(ctx->d_cd);
     delete ctx;
 }
@@ -268,6 +275,16 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
         }
         INIT_TRY(hipMalloc(&ctx->d_dz[0], MB * widest * sizeof(float)));
         INIT_TRY(hipMalloc(&ctx->d_dz[1], MB * widest * sizeof(float)));
+        if (cfg->gemm_in == NETMAX_BF16) {
+            for (int l = 0; l < cfg->n_layers; ++l) {
+                if (l > 0) INIT_TRY(hipMalloc(&ctx->d_hb[l], MB * cfg->dims[l] * sizeof(uint16_t)));
+                INIT_TRY(hipMalloc(&ctx->d_ht[l], MB * cfg->dims[l] * sizeof(uint16_t)));
+            }
+            for (int q = 0; q < 2; ++q) {
+                INIT_TRY(hipMalloc(&ctx->d_dzb[q], MB * widest * sizeof(uint16_t)));
+                INIT_TRY(hipMalloc(&ctx->d_dzt[q], MB * widest * sizeof(uint16_t)));
+            }
+        }
         INIT_TRY(hipMalloc(&ctx->d_idx, MB * sizeof(int32_t)));
         INIT_TRY(hipMalloc(&ctx->d_row0, M * sizeof(int64_t)));
         INIT_TRY(hipMalloc(&ctx->d_nrows, M * sizeof(int32_t)));
@@ -436,7 +453,11 @@ extern "C" int netmax_local_step(netmax_ctx *ctx, uint64_t iter)
     launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
     MlpPlan p{};
     p.M = c.M; p.n_layers = c.n_layers; p.B = c.batch; p.ld = c.ld; p.bf16 = (c.gemm_in == NETMAX_BF16);
-    for (int l = 0; l <= c.n_layers; ++l) { p.dims[l] = c.dims[l]; p.woff[l] = ctx->woff[l]; p.act[l] = ctx->d_act[l]; }
+    for (int l = 0; l <= c.n_layers; ++l) {
+        p.dims[l] = c.dims[l]; p.woff[l] = ctx->woff[l]; p.act[l] = ctx->d_act[l];
+        p.hb[l] = ctx->d_hb[l]; p.ht[l] = ctx->d_ht[l];
+    }
+    for (int q = 0; q < 2; ++q) { p.dzb[q] = ctx->d_dzb[q]; p.dzt[q] = ctx->d_dzt[q]; }
     p.feats = ctx->feats; p.labels = ctx->labels; p.row0 = ctx->d_row0; p.idx = ctx->d_idx;
     p.dz[0] = ctx->d_dz[0]; p.dz[1] = ctx->d_dz[1]; p.loss = ctx->d_loss;
     launch_mlp_grad(ctx->stream, p, ctx->x_cur, ctx->g);

@@ -166,6 +166,9 @@ GRAD_CASES = [
     ("cfg5", dict(M=4, n_per_worker=256, dims=(512, 256, 128, 10))),
     ("cfg5", dict(M=3, batch=37, n_per_worker=50, dims=(96, 40, 24, 10))),
     ("cfg5", dict(M=2, n_per_worker=300, dims=(3072, 1024, 1024, 10))),      # the full layer shapes
+    ("cfg5", dict(M=5, batch=64, n_per_worker=100, dims=(256, 384, 128, 10))),   # matrix-core path, batch < 128
+    ("cfg5", dict(M=3, batch=32, n_per_worker=40, dims=(128, 128, 256))),        # ... also for the last layer
+    ("cfg5", dict(M=3, batch=96, n_per_worker=200, dims=(384, 128))),            # softmax regression, bf16
 ]
 
 # Gradient tolerances, relative L2 per worker.  fp32 operands: fp32 accumulation over at most a few
