@@ -15,11 +15,11 @@ __device__ __forceinline__ Words4 philox4x32_10(uint32_t c0, uint32_t c1, uint32
     constexpr uint32_t WEYL_0 = 0x9E3779B9u, WEYL_1 = 0xBB67AE85u;
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
-        const uint32_t hiA = __umulhi(MUL_A, c0), loA = MUL_A * c0;
-        const uint32_t hiB = __umulhi(MUL_B, c2), loB = MUL_B * c2;
-        const uint32_t t0 = hiB ^ c1 ^ k0;
-        const uint32_t t2 = hiA ^ c3 ^ k1;
-        c0 = t0; c1 = loB; c2 = t2; c3 = loA;
+        // full 64-bit products: one v_mad_u64_u32 each instead of a high and a low multiply
+        const uint64_t prodA = (uint64_t)MUL_A * c0, prodB = (uint64_t)MUL_B * c2;
+        const uint32_t t0 = (uint32_t)(prodB >> 32) ^ c1 ^ k0;
+        const uint32_t t2 = (uint32_t)(prodA >> 32) ^ c3 ^ k1;
+        c0 = t0; c1 = (uint32_t)prodB; c2 = t2; c3 = (uint32_t)prodA;
         k0 += WEYL_0; k1 += WEYL_1;
     }
     return Words4{c0, c1, c2, c3};
