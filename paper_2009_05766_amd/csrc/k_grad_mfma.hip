@@ -20,9 +20,14 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int MF_THREADS = 256;      // 4 waves, arranged 2 x 2 over a 128 x 128 output tile
-constexpr int MF_BM = 128, MF_BN = 128, MF_BK = 32;
-constexpr int MF_PITCH = MF_BK + 8;  // LDS row pitch in bf16 elements (80 B: 16-byte aligned, conflict-free b128 reads)
+constexpr int MF_THREADS = 256;      // 4 waves
+constexpr int MF_BM = 128, MF_BN = 128;        // weight-gradient and forward tile
+constexpr int MF_BK = 32;                      // forward: contraction step
+constexpr int MF_PITCH = MF_BK + 8;            // 80 B rows: 16-byte aligned, conflict-free b128 reads
+// backward-data tile: 64 batch rows x 128 columns per workgroup, contraction in steps of 64;
+// waves 2 x 2, each 32 rows x 64 columns.  Two workgroups share a 128-row batch and the same weight block.
+constexpr int FD_BM = 64, FD_BN = 128, FD_BK = 64;
+constexpr int FD_PITCH = FD_BK + 8;  // LDS row pitch in bf16 elements (144 B: 16-byte aligned, conflict-free b128 reads)
 
 __device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 acc)
 {
@@ -31,8 +36,42 @@ __device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 acc)
 
 __device__ __forceinline__ int d_row(int lane, int v) { return 4 * (lane >> 5) + (v & 3) + 8 * (v >> 2); }
 
-// One K step of the 128 x 128 tile from LDS: As[m][k], Bs[n][k], both k-contiguous.
-__device__ __forceinline__ void tile_mma(const uint16_t (*As)[MF_PITCH], const uint16_t (*Bs)[MF_PITCH], int wm, int wn,
+// Workgroup id -> (worker, block inside the worker's GEMM).  Workgroup ids are dealt round-robin to the 8
+// XCDs; all blocks of one worker are placed on the same XCD, next to each other, so the operand every
+// block of that worker re-reads (its activations / back-propagated errors) comes from HBM once and from
+// that XCD's L2 afterwards.  Returns false for the padding ids beyond the last worker.
+constexpr int MF_XCD = 8;
+__device__ __forceinline__ bool decode_group(unsigned bid, unsigned blocks_per_worker, int M, int &g, unsigned &local)
+{
+    const unsigned xcd = bid % MF_XCD, slot = bid / MF_XCD;
+    const unsigned round = slot / blocks_per_worker;
+    local = slot - round * blocks_per_worker;
+    g = (int)(round * MF_XCD + xcd);
+    return g < M;
+}
+static unsigned grouped_grid(int M, unsigned blocks_per_worker)
+{
+    return (unsigned)((M + MF_XCD - 1) / MF_XCD * MF_XCD) * blocks_per_worker;
+}
+
+// One contraction step of the 64 x 128 tile from LDS: As[m][k], Bs[n][k], both k-contiguous.
+__device__ __forceinline__ void tile_mma(const uint16_t (*As)[FD_PITCH], const uint16_t (*Bs)[FD_PITCH], int wm, int wn,
+                                         int lane, f32x16 (&acc)[2])
+{
+#pragma unroll
+    for (int ks = 0; ks < FD_BK / 16; ++ks) {
+        const int kofs = 16 * ks + 8 * (lane >> 5);
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(&As[32 * wm + (lane & 31)][kofs]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const u32x4 b = *reinterpret_cast<const u32x4 *>(&Bs[64 * wn + 32 * j + (lane & 31)][kofs]);
+            acc[j] = mfma_bf16(a, b, acc[j]);
+        }
+    }
+}
+
+// One contraction step of the 128 x 128 forward tile from LDS: As[m][k], Bs[n][k], both k-contiguous.
+__device__ __forceinline__ void tile_mma_128(const uint16_t (*As)[MF_PITCH], const uint16_t (*Bs)[MF_PITCH], int wm, int wn,
                                          int lane, f32x16 (&acc)[2][2])
 {
 #pragma unroll
@@ -64,12 +103,15 @@ struct FwdMfmaArgs {
 };
 
 template <bool FIRST>
-__global__ void __launch_bounds__(MF_THREADS) fwd_mfma_kernel(FwdMfmaArgs p)
+__global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) fwd_mfma_kernel(FwdMfmaArgs p)
 {
     __shared__ __attribute__((aligned(16))) uint16_t As[MF_BM][MF_PITCH];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[MF_BN][MF_PITCH];
-    const int g = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const int64_t n0 = (int64_t)blockIdx.x * MF_BN;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    int g;
+    unsigned nblk;
+    if (!decode_group(blockIdx.x, (unsigned)(p.dout / MF_BN), p.M, g, nblk)) return;
+    const int64_t n0 = (int64_t)nblk * MF_BN;
 
     // A: two 16-byte chunks per thread: rows ar[c], k offset 8 * (chunk % 4)
     const uint16_t *a_src[2];
@@ -126,7 +168,7 @@ __global__ void __launch_bounds__(MF_THREADS) fwd_mfma_kernel(FwdMfmaArgs p)
         stash();
         __syncthreads();
         if (k0 + MF_BK < p.din) fetch(k0 + MF_BK);   // overlaps with the matrix instructions below
-        tile_mma(As, Bs, wm, wn, lane, acc);
+        tile_mma_128(As, Bs, wm, wn, lane, acc);
     }
 
     // epilogue: bias, ReLU, bf16, both layouts
@@ -160,8 +202,9 @@ __global__ void __launch_bounds__(MF_THREADS) fwd_mfma_kernel(FwdMfmaArgs p)
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Backward through a layer: dA = (dZ W^T) * [A > 0] for one worker and 128 input features (output columns).
-// dZ: bf16 [B][dout]; W rows are contiguous along the contraction index, so they go to LDS untransposed.
+// Backward through a layer: dA = (dZ W^T) * [A > 0] for one worker, 64 batch rows and 128 input features
+// (the output columns).  dZ: bf16 [B][dout]; W rows are contiguous along the contraction index, so they go
+// to LDS untransposed (256-byte row pieces per step).
 // Output: fp32 [B][din] (for the bias gradient), bf16 [B][din] and bf16 transposed [din][B].
 struct DgradMfmaArgs {
     const uint16_t *dz; const float *X; int64_t woff; int M, B; int64_t din, dout;
@@ -171,61 +214,64 @@ struct DgradMfmaArgs {
 
 __global__ void __launch_bounds__(MF_THREADS) dgrad_mfma_kernel(DgradMfmaArgs p)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t As[MF_BM][MF_PITCH];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[MF_BN][MF_PITCH];
-    const int g = blockIdx.y, t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const int64_t c0 = (int64_t)blockIdx.x * MF_BN;       // first input feature (output column) of this block
+    __shared__ __attribute__((aligned(16))) uint16_t As[FD_BM][FD_PITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[FD_BN][FD_PITCH];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const unsigned mblocks = (unsigned)((p.B + FD_BM - 1) / FD_BM);
+    int g;
+    unsigned local;
+    if (!decode_group(blockIdx.x, (unsigned)(p.din / FD_BN) * mblocks, p.M, g, local)) return;
+    const int64_t c0 = (int64_t)(local / mblocks) * FD_BN;     // first input feature (output column) of this block
+    const int m0 = (int)(local % mblocks) * FD_BM;
 
     const uint16_t *a_src[2];
     int a_row[2], a_k[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
         const int chunk = t + c * MF_THREADS;
-        a_row[c] = chunk >> 2;
-        a_k[c] = (chunk & 3) * 8;
-        a_src[c] = a_row[c] < p.B ? p.dz + ((size_t)g * p.B + a_row[c]) * p.dout + a_k[c] : nullptr;
+        a_row[c] = chunk >> 3;
+        a_k[c] = (chunk & 7) * 8;
+        a_src[c] = m0 + a_row[c] < p.B ? p.dz + ((size_t)g * p.B + m0 + a_row[c]) * p.dout + a_k[c] : nullptr;
     }
-    // W: four 128-bit loads per thread, chunk = t + 256 r: feature row = chunk / 8, quad = chunk % 8
-    f32x16 acc[2][2];
+    f32x16 acc[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
+    // W: eight 128-bit loads per thread, chunk = t + 256 r: feature row = chunk / 16, quad = chunk % 16
     u32x4 ra[2];
-    f32x4_t rw[4];
+    f32x4_t rw[8];
     auto fetch = [&](int64_t k0) {
 #pragma unroll
         for (int c = 0; c < 2; ++c)
             ra[c] = a_src[c] ? *reinterpret_cast<const u32x4 *>(a_src[c] + k0) : (u32x4){0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 8; ++r) {
             const int chunk = t + r * MF_THREADS;
-            const int64_t feat = c0 + (chunk >> 3);
-            rw[r] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, p.woff + feat * p.dout + k0 + 4 * (chunk & 7)));
+            const int64_t feat = c0 + (chunk >> 4);
+            rw[r] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, p.woff + feat * p.dout + k0 + 4 * (chunk & 15)));
         }
     };
     auto stash = [&]() {
 #pragma unroll
         for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4 *>(&As[a_row[c]][a_k[c]]) = ra[c];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 8; ++r) {
             const int chunk = t + r * MF_THREADS;
             u32x2 packed;
             packed.x = pack_bf16x2(rw[r][0], rw[r][1]);
             packed.y = pack_bf16x2(rw[r][2], rw[r][3]);
-            *reinterpret_cast<u32x2 *>(&Bs[chunk >> 3][4 * (chunk & 7)]) = packed;
+            *reinterpret_cast<u32x2 *>(&Bs[chunk >> 4][4 * (chunk & 15)]) = packed;
         }
     };
 
     fetch(0);
-    for (int64_t k0 = 0; k0 < p.dout; k0 += MF_BK) {
+    for (int64_t k0 = 0; k0 < p.dout; k0 += FD_BK) {
         __syncthreads();
         stash();
         __syncthreads();
-        if (k0 + MF_BK < p.dout) fetch(k0 + MF_BK);
+        if (k0 + FD_BK < p.dout) fetch(k0 + FD_BK);
         tile_mma(As, Bs, wm, wn, lane, acc);
     }
 
@@ -233,79 +279,116 @@ __global__ void __launch_bounds__(MF_THREADS) dgrad_mfma_kernel(DgradMfmaArgs p)
     for (int j = 0; j < 2; ++j) {
         const int64_t col = c0 + 64 * wn + 32 * j + (lane & 31);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int q = 0; q < 4; ++q) {
+            const int row = m0 + 32 * wm + d_row(lane, 4 * q);
+            if (row + 3 < p.B) {
+                float d[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int row = 64 * wm + 32 * i + d_row(lane, 4 * q);
-                if (row + 3 < p.B) {
-                    float d[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const size_t at = ((size_t)g * p.B + row + e) * p.din + col;
-                        d[e] = bf16_positive(p.act[at]) ? acc[i][j][4 * q + e] : 0.0f;
-                        p.out_f32[at] = d[e];
-                        p.out[at] = (uint16_t)bf16_bits(d[e]);
-                    }
-                    u32x2 packed;
-                    packed.x = pack_bf16x2(d[0], d[1]);
-                    packed.y = pack_bf16x2(d[2], d[3]);
-                    *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.din + col) * p.B + row) = packed;
+                for (int e = 0; e < 4; ++e) {
+                    const size_t at = ((size_t)g * p.B + row + e) * p.din + col;
+                    d[e] = bf16_positive(p.act[at]) ? acc[j][4 * q + e] : 0.0f;
+                    p.out_f32[at] = d[e];
+                    p.out[at] = (uint16_t)bf16_bits(d[e]);
                 }
+                u32x2 packed;
+                packed.x = pack_bf16x2(d[0], d[1]);
+                packed.y = pack_bf16x2(d[2], d[3]);
+                *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.din + col) * p.B + row) = packed;
             }
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Weight gradient: dW = A^T dZ for one worker and one 128 x 128 block of W.  The contraction runs over
-// the batch (<= 128), so both operands are small: each lane reads its matrix-instruction operands
-// straight from the transposed bf16 copies A^T [din][B] and dZ^T [dout][B] (batch-contiguous, L2
-// resident); the product is written once, fp32, into the gradient row (tile layout).
+// Weight gradient: dW = A^T dZ for one worker and a strip of 128 rows of W.  The contraction runs over
+// the batch (<= 128), so whole operand blocks fit in LDS: the strip's A^T block [128][B] is loaded once,
+// then the workgroup walks along the strip in blocks of 128 columns; the dZ^T block of the next step is
+// fetched into registers while the matrix instructions of the current one run.  Both operands are the
+// transposed bf16 copies (batch-contiguous), read with coalesced 128-bit loads.  The fp32 product leaves
+// straight from the accumulators as 128-byte row pieces (non-temporal) into the gradient row.
 struct WgradMfmaArgs {
     const uint16_t *a_t, *dz_t; int M, B; int64_t din, dout, woff; float *G;
 };
 
+constexpr int WG_PITCH = 128 + 8;            // bf16 elements per operand row in LDS (272 B)
+constexpr int WG_CHUNKS = MF_BM * 128 / 8 / MF_THREADS;   // 16-byte chunks per thread and operand block at B = 128
+
 __global__ void __launch_bounds__(MF_THREADS) wgrad_mfma_kernel(WgradMfmaArgs p)
 {
-    const int g = blockIdx.z, t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const int64_t r0 = (int64_t)blockIdx.y * MF_BM + 64 * wm, n0 = (int64_t)blockIdx.x * MF_BN + 64 * wn;
-    const uint16_t *a_ptr[2], *b_ptr[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) a_ptr[i] = p.a_t + ((size_t)g * p.din + r0 + 32 * i + (lane & 31)) * p.B + 8 * (lane >> 5);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) b_ptr[j] = p.dz_t + ((size_t)g * p.dout + n0 + 32 * j + (lane & 31)) * p.B + 8 * (lane >> 5);
+    __shared__ __attribute__((aligned(16))) uint16_t At[MF_BM][WG_PITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t Zt[MF_BN][WG_PITCH];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const unsigned nx = (unsigned)(p.dout / MF_BN), ny = (unsigned)(p.din / MF_BM);
+    int g;
+    unsigned strip;
+    if (!decode_group(blockIdx.x, ny, p.M, g, strip)) return;
+    const int64_t r0 = (int64_t)strip * MF_BM;
+    const int chunks_per_row = p.B >> 3;                        // 16-byte chunks; at most 16
+    const int n_chunks = MF_BM * chunks_per_row;
+    const uint16_t *a_src = p.a_t + ((size_t)g * p.din + r0) * p.B;
+    const uint16_t *z_src = p.dz_t + (size_t)g * p.dout * p.B;
 
-    f32x16 acc[2][2];
+    int c_row[WG_CHUNKS], c_col[WG_CHUNKS];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int q = 0; q < WG_CHUNKS; ++q) {
+        const int c = t + q * MF_THREADS;
+        c_row[q] = c / chunks_per_row;
+        c_col[q] = (c - c_row[q] * chunks_per_row) * 8;
+    }
+    u32x4 rz[WG_CHUNKS];
+    auto fetch_z = [&](unsigned nb) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int q = 0; q < WG_CHUNKS; ++q)
+            if (t + q * MF_THREADS < n_chunks)
+                rz[q] = *reinterpret_cast<const u32x4 *>(z_src + ((size_t)nb * MF_BN + c_row[q]) * p.B + c_col[q]);
+    };
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    for (int q = 0; q < WG_CHUNKS; ++q)
+        if (t + q * MF_THREADS < n_chunks)
+            *reinterpret_cast<u32x4 *>(&At[c_row[q]][c_col[q]]) =
+                *reinterpret_cast<const u32x4 *>(a_src + (size_t)c_row[q] * p.B + c_col[q]);
+    fetch_z(0);
 
-    for (int b0 = 0; b0 < p.B; b0 += 16) {
-        u32x4 a[2], b[2];
+    for (unsigned nb = 0; nb < nx; ++nb) {
+        __syncthreads();                                        // the previous block's reads of Zt are done
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const u32x4 *>(a_ptr[i] + b0);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(b_ptr[j] + b0);
+        for (int q = 0; q < WG_CHUNKS; ++q)
+            if (t + q * MF_THREADS < n_chunks) *reinterpret_cast<u32x4 *>(&Zt[c_row[q]][c_col[q]]) = rz[q];
+        __syncthreads();
+        if (nb + 1 < nx) fetch_z(nb + 1);
+
+        f32x16 acc[2][2];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
-    }
-
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        for (int b0 = 0; b0 < p.B; b0 += 16) {
+            const int kofs = b0 + 8 * (lane >> 5);
+            u32x4 a[2], b[2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t col = n0 + 32 * j + (lane & 31);
+            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const u32x4 *>(&At[64 * wm + 32 * i + (lane & 31)][kofs]);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = r0 + 32 * i + d_row(lane, v);
-                __builtin_nontemporal_store(acc[i][j][v], p.G + tiled_offset(p.M, g, p.woff + row * p.dout + col));
-            }
+            for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&Zt[64 * wn + 32 * j + (lane & 31)][kofs]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
         }
+        const int64_t n0 = (int64_t)nb * MF_BN + 64 * wn;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int64_t col = n0 + 32 * j + (lane & 31);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t row = r0 + 64 * wm + 32 * i + d_row(lane, v);
+                    __builtin_nontemporal_store(acc[i][j][v], p.G + tiled_offset(p.M, g, p.woff + row * p.dout + col));
+                }
+            }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -353,7 +436,7 @@ gather_transpose_kernel(const uint16_t *__restrict__ feats, const int64_t *__res
 bool mfma_layer_ok(const MlpPlan &p, int l)
 {
     const int64_t din = p.dims[l], dout = p.dims[l + 1];
-    return p.bf16 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && dout % 128 == 0 && p.woff[l] % 4 == 0;
+    return p.bf16 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && dout % 128 == 0 && p.woff[l] % 4 == 0;   // din % 128 covers FD_BK
 }
 
 void launch_gather_transpose(hipStream_t s, const MlpPlan &p)
@@ -368,7 +451,7 @@ void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X)
     a.feats = (const uint16_t *)p.feats; a.row0 = p.row0; a.idx = p.idx; a.a_prev = l > 0 ? p.hb[l] : nullptr;
     a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.relu = (l + 1 < p.n_layers); a.out = p.hb[l + 1]; a.out_t = p.ht[l + 1];
-    const dim3 grid((unsigned)(a.dout / MF_BN), p.M);
+    const dim3 grid(grouped_grid(p.M, (unsigned)(a.dout / MF_BN)));
     if (l == 0) hipLaunchKernelGGL(fwd_mfma_kernel<true>, grid, dim3(MF_THREADS), 0, s, a);
     else hipLaunchKernelGGL(fwd_mfma_kernel<false>, grid, dim3(MF_THREADS), 0, s, a);
 }
@@ -378,7 +461,9 @@ void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, i
     DgradMfmaArgs a;
     a.dz = p.dzb[cur]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.act = p.hb[l]; a.out_f32 = p.dz[cur ^ 1]; a.out = p.dzb[cur ^ 1]; a.out_t = p.dzt[cur ^ 1];
-    hipLaunchKernelGGL(dgrad_mfma_kernel, dim3((unsigned)(a.din / MF_BN), p.M), dim3(MF_THREADS), 0, s, a);
+    hipLaunchKernelGGL(dgrad_mfma_kernel,
+                       dim3(grouped_grid(p.M, (unsigned)(a.din / FD_BN) * (unsigned)((p.B + FD_BM - 1) / FD_BM))),
+                       dim3(MF_THREADS), 0, s, a);
 }
 
 void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur)
@@ -386,8 +471,7 @@ void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur
     WgradMfmaArgs a;
     a.a_t = p.ht[l]; a.dz_t = p.dzt[cur]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.woff = p.woff[l]; a.G = G;
-    hipLaunchKernelGGL(wgrad_mfma_kernel, dim3((unsigned)(a.dout / MF_BN), (unsigned)(a.din / MF_BM), p.M),
-                       dim3(MF_THREADS), 0, s, a);
+    hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / MF_BM))), dim3(MF_THREADS), 0, s, a);
 }
 
 }  // namespace netmax
