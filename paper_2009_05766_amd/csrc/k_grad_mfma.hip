@@ -433,10 +433,201 @@ gather_transpose_kernel(const uint16_t *__restrict__ feats, const int64_t *__res
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Last layer with few classes (dout <= 32): the same three products with the class dimension padded to
+// one 32-wide matrix-instruction tile.  The weight matrix is tiny (din x dout), the work is bound by
+// reading / writing the [B][din] activations and errors.
+
+// logits = A W + b.  One workgroup per worker; W^T goes to LDS as bf16 [32][din], each wave takes 32
+// batch rows and reads its A operands straight from the bf16 activations.
+struct FwdSmallArgs {
+    const uint16_t *a_prev; const float *X; int64_t woff; int M, B; int64_t din, dout; float *out;
+};
+constexpr int SMALL_MAX_DIN = 2048;
+
+__global__ void __launch_bounds__(MF_THREADS) fwd_small_mfma_kernel(FwdSmallArgs p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t Wt[];      // [32][din + 8]
+    const int g = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int pitch = (int)p.din + 8;
+    for (int e = t; e < 32 * pitch / 2; e += MF_THREADS) reinterpret_cast<uint32_t *>(Wt)[e] = 0u;
+    __syncthreads();
+    const int64_t n_w = p.din * p.dout;
+    for (int64_t e = t; e < n_w; e += MF_THREADS) {
+        const int64_t k = e / p.dout;
+        const int n = (int)(e - k * p.dout);
+        Wt[n * pitch + k] = (uint16_t)bf16_bits(p.X[tiled_offset(p.M, g, p.woff + e)]);
+    }
+    __syncthreads();
+    for (int m0 = 32 * wave; m0 < p.B; m0 += 32 * (MF_THREADS / 64)) {
+        const uint16_t *a_ptr = p.a_prev + ((size_t)g * p.B + m0 + (lane & 31)) * p.din + 8 * (lane >> 5);
+        const uint16_t *b_ptr = Wt + (lane & 31) * pitch + 8 * (lane >> 5);
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        for (int64_t k0 = 0; k0 < p.din; k0 += 16)
+            acc = mfma_bf16(*reinterpret_cast<const u32x4 *>(a_ptr + k0), *reinterpret_cast<const u32x4 *>(b_ptr + k0), acc);
+        const int col = lane & 31;
+        if (col < p.dout) {
+            const float bcol = p.X[tiled_offset(p.M, g, p.woff + n_w + col)];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) p.out[((size_t)g * p.B + m0 + d_row(lane, v)) * p.dout + col] = acc[v] + bcol;
+        }
+    }
+}
+
+// dW = A^T dZ with dout <= 32: one workgroup = one worker x 128 rows of W, one 32-row tile per wave;
+// both operands come straight from the transposed bf16 copies.
+struct WgradSmallArgs {
+    const uint16_t *a_t, *dz_t; int M, B; int64_t din, dout, woff; float *G;
+};
+
+__global__ void __launch_bounds__(MF_THREADS) wgrad_small_mfma_kernel(WgradSmallArgs p)
+{
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int g;
+    unsigned strip;
+    if (!decode_group(blockIdx.x, (unsigned)(p.din / 128), p.M, g, strip)) return;
+    const int64_t r0 = (int64_t)strip * 128 + 32 * wave;
+    const uint16_t *a_ptr = p.a_t + ((size_t)g * p.din + r0 + (lane & 31)) * p.B + 8 * (lane >> 5);
+    const int n = lane & 31;
+    const uint16_t *b_ptr = p.dz_t + ((size_t)g * p.dout + n) * p.B + 8 * (lane >> 5);
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    for (int b0 = 0; b0 < p.B; b0 += 16) {
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(a_ptr + b0);
+        const u32x4 b = n < p.dout ? *reinterpret_cast<const u32x4 *>(b_ptr + b0) : (u32x4){0u, 0u, 0u, 0u};
+        acc = mfma_bf16(a, b, acc);
+    }
+    if (n < p.dout) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            p.G[tiled_offset(p.M, g, p.woff + (r0 + d_row(lane, v)) * p.dout + n)] = acc[v];
+    }
+}
+
+// dA = (dZ W^T) * [A > 0] with dout <= 32: the contraction is one or two matrix-instruction steps.
+// One workgroup = one worker x 128 input features x all batch rows; waves 2 x 2, 64 x 64 each.
+struct DgradSmallArgs {
+    const uint16_t *dz; const float *X; int64_t woff; int M, B; int64_t din, dout;
+    const uint16_t *act; float *out_f32; uint16_t *out, *out_t;
+};
+
+__global__ void __launch_bounds__(MF_THREADS) dgrad_small_mfma_kernel(DgradSmallArgs p)
+{
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    int g;
+    unsigned cblk;
+    if (!decode_group(blockIdx.x, (unsigned)(p.din / 128), p.M, g, cblk)) return;
+    const int64_t c0 = (int64_t)cblk * 128 + 64 * wn;
+    const int steps = p.dout <= 16 ? 1 : 2;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    for (int s = 0; s < steps; ++s) {
+        const int nbase = 16 * s + 8 * (lane >> 5);
+        u32x4 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = 64 * wm + 32 * i + (lane & 31);
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                h[e] = (row < p.B && nbase + e < p.dout) ? p.dz[((size_t)g * p.B + row) * p.dout + nbase + e] : 0u;
+            a[i] = (u32x4){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t feat = c0 + 32 * j + (lane & 31);
+            float w[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                w[e] = nbase + e < p.dout ? p.X[tiled_offset(p.M, g, p.woff + feat * p.dout + nbase + e)] : 0.0f;
+            b[j] = (u32x4){pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]), pack_bf16x2(w[4], w[5]), pack_bf16x2(w[6], w[7])};
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t col = c0 + 32 * j + (lane & 31);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = 64 * wm + 32 * i + d_row(lane, 4 * q);
+                if (row + 3 < p.B) {
+                    float d[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const size_t at = ((size_t)g * p.B + row + e) * p.din + col;
+                        d[e] = bf16_positive(p.act[at]) ? acc[i][j][4 * q + e] : 0.0f;
+                        p.out_f32[at] = d[e];
+                        p.out[at] = (uint16_t)bf16_bits(d[e]);
+                    }
+                    u32x2 packed;
+                    packed.x = pack_bf16x2(d[0], d[1]);
+                    packed.y = pack_bf16x2(d[2], d[3]);
+                    *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.din + col) * p.B + row) = packed;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
 bool mfma_layer_ok(const MlpPlan &p, int l)
 {
     const int64_t din = p.dims[l], dout = p.dims[l + 1];
     return p.bf16 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && dout % 128 == 0 && p.woff[l] % 4 == 0;   // din % 128 covers FD_BK
+}
+
+// the last layer when it has at most 32 outputs (see the "few classes" kernels above)
+bool mfma_small_last_ok(const MlpPlan &p)
+{
+    const int l = p.n_layers - 1;
+    const int64_t din = p.dims[l], dout = p.dims[l + 1];
+    return p.bf16 && l > 0 && dout <= 32 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && din <= SMALL_MAX_DIN;
+}
+
+void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X)
+{
+    const int l = p.n_layers - 1;
+    FwdSmallArgs a;
+    a.a_prev = p.hb[l]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
+    a.out = p.act[l + 1];
+    const size_t lds = (size_t)32 * (a.din + 8) * sizeof(uint16_t);
+    static bool raised = false;
+    if (!raised) {   // more than the default 64 KB of dynamic LDS
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_small_mfma_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 32 * (SMALL_MAX_DIN + 8) * 2);
+        raised = true;
+    }
+    hipLaunchKernelGGL(fwd_small_mfma_kernel, dim3(p.M), dim3(MF_THREADS), lds, s, a);
+}
+
+void launch_wgrad_small(hipStream_t s, const MlpPlan &p, float *G, int cur)
+{
+    const int l = p.n_layers - 1;
+    WgradSmallArgs a;
+    a.a_t = p.ht[l]; a.dz_t = p.dzt[cur]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
+    a.woff = p.woff[l]; a.G = G;
+    hipLaunchKernelGGL(wgrad_small_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / 128))), dim3(MF_THREADS), 0, s, a);
+}
+
+void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, int cur)
+{
+    const int l = p.n_layers - 1;
+    DgradSmallArgs a;
+    a.dz = p.dzb[cur]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
+    a.act = p.hb[l]; a.out_f32 = p.dz[cur ^ 1]; a.out = p.dzb[cur ^ 1]; a.out_t = p.dzt[cur ^ 1];
+    hipLaunchKernelGGL(dgrad_small_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / 128))), dim3(MF_THREADS), 0, s, a);
 }
 
 void launch_gather_transpose(hipStream_t s, const MlpPlan &p)

@@ -233,6 +233,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
     const bool bf = p.bf16 != 0;
     bool fast[8] = {};
     for (int l = 0; l < L; ++l) fast[l] = mfma_layer_ok(p, l);
+    const bool small_last = mfma_small_last_ok(p);
     auto input_of = [&](int l) {
         LayerInput in;
         in.feats = p.feats; in.feats_bf16 = p.bf16; in.row0 = p.row0; in.idx = p.idx;
@@ -247,6 +248,10 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
         const bool last = (l + 1 == L);
         if (fast[l] && !last) {
             launch_fwd_mfma(s, p, l, X);
+            continue;
+        }
+        if (last && small_last) {
+            launch_fwd_small(s, p, X);
             continue;
         }
         FwdProblem f;
@@ -267,6 +272,8 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
         const int64_t din = p.dims[l], dout = p.dims[l + 1];
         if (fast[l]) {
             launch_wgrad_mfma(s, p, l, G, cur);
+        } else if (l == L - 1 && small_last) {
+            launch_wgrad_small(s, p, G, cur);
         } else {
             WgradProblem wg;
             wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
@@ -279,6 +286,8 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
         if (l > 0) {
             if (fast[l]) {
                 launch_dgrad_mfma(s, p, l, X, cur);
+            } else if (l == L - 1 && small_last) {
+                launch_dgrad_small(s, p, X, cur);
             } else {
                 DgradProblem dg;
                 dg.dz = p.dz[cur]; dg.X = X; dg.act = bf ? nullptr : p.act[l]; dg.act_bf16 = bf ? p.hb[l] : nullptr;

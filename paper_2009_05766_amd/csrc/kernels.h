@@ -60,5 +60,10 @@ void launch_gather_transpose(hipStream_t s, const MlpPlan &p);
 void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X);
 void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, int cur);
 void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur);
+// Last layer with at most 32 outputs.
+bool mfma_small_last_ok(const MlpPlan &p);
+void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X);
+void launch_wgrad_small(hipStream_t s, const MlpPlan &p, float *G, int cur);
+void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, int cur);
 
 }  // namespace netmax
