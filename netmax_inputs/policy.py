@@ -80,3 +80,15 @@ def policy_for(w: Workload):
         P = floor_and_renormalise(P, 1.0 / (4.0 * w.M))
     rho = float(np.float32(default_rho(P, w.lr)))
     return P, rho
+
+
+def iteration_times(recipe: str, M: int, seed: int = BASE_SEED, compute: float = 0.05) -> np.ndarray:
+    """Synthetic iteration-time matrix for policy generation: t_im = max(C, N_im) with the communication time
+    N_im inversely proportional to the link speed (fastest link = 1 time unit) and a common compute time C
+    (Section II-B "Iteration time"); the diagonal holds C, the duration of an iteration without a pull."""
+    s = link_speeds(recipe, M, seed)
+    with np.errstate(divide="ignore"):
+        n = np.where(s > 0, s.max() / s, 0.0)
+    t = np.maximum(n, compute)
+    np.fill_diagonal(t, compute)
+    return t
