@@ -97,6 +97,19 @@ int netmax_init(netmax_ctx **out, const netmax_config *cfg);
 int netmax_build_tables(int32_t M, const double *P, const uint8_t *adj, float lr, float rho, int32_t strict_o3,
                         uint32_t *thresholds_host, int32_t *last_host, float *w_host);
 
+/* Communication policy generation (Algorithm 3; Section III-C; Appendix A), host only, no GPU needed.
+ * t_host: host double [M][M], t_im = iteration time of worker i when it pulls from m (the diagonal is ignored:
+ * d_ii = 0 in Eq. (d3)); adj as in netmax_config; alpha = learning rate; K, R = grid sizes of the outer
+ * (rho = k 0.5 / (alpha K), k = 1..K) and inner (tbar = L + r (U - L) / R, r = 1..R) search; eps in (0,1) scales
+ * T_convergence = tbar ln(eps) / ln(lambda_2).  For every grid point the row-separable linear program
+ * min sum p_ii s.t. (o2)-(o5) is solved ((o3) with >=; among the optimal points the one with the least-squares
+ * distance to the lower bounds of (o3)), lambda_2 is the second largest eigenvalue of Y_P (Eq. (d2)).
+ * Outputs (host): P_out double [M][M], rho_out; optional tbar_out, lambda2_out, t_conv_out of the winner.
+ * Returns NETMAX_OK, NETMAX_EINVAL, or NETMAX_EINFEASIBLE if no grid point is feasible. */
+int netmax_generate_policy(int32_t M, const double *t_host, const uint8_t *adj, double alpha, int32_t K, int32_t R,
+                           double eps, double *P_out, double *rho_out, double *tbar_out, double *lambda2_out,
+                           double *t_conv_out);
+
 /* A new policy and weight from the monitor takes effect at the next iteration (Algorithm 2, "received
  * new policy").  P: host, M*M.  The tables are rebuilt; on error the old ones stay in force. */
 int netmax_set_policy(netmax_ctx *ctx, const double *P, float rho);

@@ -20,7 +20,7 @@ NETMAX_FLAT, NETMAX_MLP = 0, 1
 NETMAX_F32, NETMAX_BF16 = 0, 1
 
 EXPORTS = (
-    "netmax_init", "netmax_build_tables", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
+    "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
     "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix",
     "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
@@ -61,6 +61,7 @@ def load():
     sig = {
         "netmax_init": (C.c_int, [C.POINTER(vp), C.POINTER(netmax_config)]),
         "netmax_build_tables": (C.c_int, [i32, vp, vp, f32, f32, i32, vp, vp, vp]),
+        "netmax_generate_policy": (C.c_int, [i32, vp, vp, C.c_double, i32, i32, C.c_double, vp, vp, vp, vp, vp]),
         "netmax_set_policy": (C.c_int, [vp, vp, f32]),
         "netmax_set_lr": (C.c_int, [vp, f32]),
         "netmax_bind_state": (C.c_int, [vp, vp, vp, vp, vp]),
@@ -124,6 +125,21 @@ def netmax_build_tables(P: np.ndarray, adj: Optional[np.ndarray], lr: float, rho
     w = np.empty((M, M), np.float32)
     _check(load().netmax_build_tables(M, _hp(P), _hp(adj), lr, rho, int(strict_o3), _hp(thr), _hp(last), _hp(w)))
     return thr, last, w
+
+
+def netmax_generate_policy(t: np.ndarray, alpha: float, K: int, R: int, adj: Optional[np.ndarray] = None,
+                           eps: float = 1e-3):
+    """-> dict(P, rho, tbar, lambda2, t_conv); raises NetmaxError(NETMAX_EINFEASIBLE) if no grid point is feasible."""
+    t = _host(t, np.float64)
+    M = t.shape[0]
+    adj = _host(adj, np.uint8)
+    P = np.empty((M, M), np.float64)
+    out = (C.c_double * 4)()
+    ptr = lambda k: C.c_void_p(C.addressof(out) + 8 * k)
+    rc = load().netmax_generate_policy(M, _hp(t), _hp(adj), alpha, K, R, eps, _hp(P), ptr(0), ptr(1), ptr(2), ptr(3))
+    if rc != NETMAX_OK:
+        raise NetmaxError(rc, "policy generation failed" if rc != NETMAX_EINFEASIBLE else "no feasible grid point")
+    return dict(P=P, rho=out[0], tbar=out[1], lambda2=out[2], t_conv=out[3])
 
 
 def netmax_init(*, M: int, D: int, ld: int, model: int, dims: Sequence[int] = (), batch: int = 0,

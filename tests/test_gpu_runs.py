@@ -245,3 +245,24 @@ def test_checkpoint_resume_is_bit_exact():
     assert np.array_equal(a.get("x").cpu().numpy(), c.get("x").cpu().numpy())
     assert np.array_equal(a.get("v").cpu().numpy(), c.get("v").cpu().numpy())
     a.close(); c.close()
+
+
+def test_generated_policy_installed_mid_run():
+    """The monitor's product (Algorithm 3) arriving during training (Algorithm 2, "received new policy"):
+    policy and rho generated from an iteration-time matrix by the library, installed after 10 iterations."""
+    import paper_2009_05766_amd as nm
+    from netmax_inputs import iteration_times
+    w = workload("cfg4", M=16, D=30000, T=30)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp)
+    t = iteration_times("four_group_12", w.M)
+    pol = nm.netmax_generate_policy(t, float(np.float32(w.lr)), 40, 6)
+    rho = float(np.float32(pol["rho"]))
+    for it in range(w.T):
+        if it == 10:
+            nm.netmax_set_policy(gpu.ctx, pol["P"], rho)
+            o.set_policy(pol["P"], rho)
+        gpu.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it))
+    assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
+    gpu.close()
