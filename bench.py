@@ -87,7 +87,7 @@ def main() -> int:
                          "(a kernel of known traffic, used to scale profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, nothing sharded); use --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU only (no collectives, nothing sharded); use --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

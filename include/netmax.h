@@ -59,6 +59,10 @@ typedef enum {
 
 typedef enum { NETMAX_FLAT = 0, NETMAX_MLP = 1 } netmax_model;
 typedef enum { NETMAX_F32 = 0, NETMAX_BF16 = 1 } netmax_dtype;
+/* Second-step weight.  NETMAX_MIX_POLICY: w_im = alpha rho (d_im + d_mi) / (2 p_im), Algorithm 2 (a rarely chosen
+ * peer weighs more).  NETMAX_MIX_FIXED: the same weight for every drawn pair, the gossip / AD-PSGD averaging that
+ * Section III-D and Section V-H run under the same peer-selection policy (fixed_weight = 1/2 is plain averaging). */
+typedef enum { NETMAX_MIX_POLICY = 0, NETMAX_MIX_FIXED = 1 } netmax_mix_mode;
 
 typedef struct {
     int32_t M;         /* workers, 2 .. 4096 */
@@ -81,6 +85,8 @@ typedef struct {
     const double *P;   /* host, M*M row-major; p_im = probability that worker i selects m (Section II-B) */
     const uint8_t *adj;/* host, M*M neighbourhood indicators d_im, or NULL = complete graph without self loops */
     void *stream;      /* hipStream_t, NULL = the null stream */
+    int32_t mix_mode;  /* netmax_mix_mode */
+    float fixed_weight;/* NETMAX_MIX_FIXED only: in [0, 1) */
 } netmax_config;
 
 /* Builds the context: validates the configuration, turns P into 32-bit fixed-point cumulative
@@ -95,7 +101,8 @@ int netmax_init(netmax_ctx **out, const netmax_config *cfg);
  * all host memory owned by the caller.  Returns NETMAX_OK, NETMAX_EINVAL or NETMAX_EINFEASIBLE; the text is
  * available from netmax_last_error(NULL). */
 int netmax_build_tables(int32_t M, const double *P, const uint8_t *adj, float lr, float rho, int32_t strict_o3,
-                        uint32_t *thresholds_host, int32_t *last_host, float *w_host);
+                        int32_t mix_mode, float fixed_weight, uint32_t *thresholds_host, int32_t *last_host,
+                        float *w_host);
 
 /* Communication policy generation (Algorithm 3; Section III-C; Appendix A), host only, no GPU needed.
  * t_host: host double [M][M], t_im = iteration time of worker i when it pulls from m (the diagonal is ignored:

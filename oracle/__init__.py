@@ -98,6 +98,14 @@ def mix_weights(P: np.ndarray, adj: Optional[np.ndarray], alpha: float, rho: flo
     return w
 
 
+def mix_weights_fixed(P: np.ndarray, weight: float) -> np.ndarray:
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    M = P.shape[0]
+    w = np.empty((M, M), dtype=np.float64)
+    lib().ora_mix_weights_fixed(C.c_int(M), _p(P), C.c_double(weight), _p(w))
+    return w
+
+
 def sample_batch(M: int, B: int, shard_off: np.ndarray, seed: int, it: int) -> np.ndarray:
     idx = np.empty((M, B), dtype=np.int32)
     lib().ora_sample_batch(C.c_int(M), C.c_int(B), _p(_chk(shard_off, np.int64)),
@@ -180,8 +188,9 @@ class Oracle:
     """State machine over the functions above: one instance = M workers of one workload."""
 
     def __init__(self, *, M, ld, D, dims, batch, lr, momentum, weight_decay, rho, grad_sigma, seed, P,
-                 adj=None, X0, feats=None, labels=None, shard_off=None, col0=0, operands_bf16=False):
+                 adj=None, X0, feats=None, labels=None, shard_off=None, col0=0, operands_bf16=False, fixed_weight=None):
         self.operands_bf16 = operands_bf16
+        self.fixed_weight = fixed_weight     # None: Algorithm 2's weights; a number: the same weight for every pair
         self.col0 = col0   # flat model: the state is a window of columns of a larger problem
         self.M, self.ld, self.D, self.dims, self.batch = M, ld, D, tuple(dims), batch
         self.lr, self.mu, self.wd, self.sigma, self.seed = float(lr), float(momentum), float(weight_decay), float(grad_sigma), int(seed)
@@ -197,7 +206,8 @@ class Oracle:
     def set_policy(self, P, rho):
         self.P, self.rho = np.ascontiguousarray(P, dtype=np.float64), float(rho)
         self.T, self.last = thresholds(self.P)
-        self.w = mix_weights(self.P, self.adj, self.lr, self.rho)
+        self.w = (mix_weights(self.P, self.adj, self.lr, self.rho) if self.fixed_weight is None
+                  else mix_weights_fixed(self.P, self.fixed_weight))
 
     def sample_peers(self, it):
         return sample_peers(self.T, self.last, self.seed, it)

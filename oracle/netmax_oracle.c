@@ -150,6 +150,15 @@ void ora_mix_weights(int M, const double *P, const uint8_t *adj, double alpha, d
         }
 }
 
+/* The fixed-weight variant: the gossip / AD-PSGD update that Section III-D and Section V-H run under the same
+ * peer-selection policy uses one weight for every pulled model (1/2 = plain averaging of the two copies). */
+void ora_mix_weights_fixed(int M, const double *P, double weight, double *w)
+{
+    for (int i = 0; i < M; ++i)
+        for (int m = 0; m < M; ++m)
+            w[(size_t)i * M + m] = (m == i || P[(size_t)i * M + m] <= 0.0) ? 0.0 : weight;
+}
+
 /* ------------------------------------------------------------------ batch indices
  * "sampled dataset D_{i,n} from D_i" (Eq. (a5)): B draws with replacement from the
  * worker's shard; draw b uses word b%4 of block b/4 of stream 1 and maps it to

@@ -18,6 +18,7 @@ NETMAX_TILE = 2048
 NETMAX_OK, NETMAX_EINVAL, NETMAX_EINFEASIBLE, NETMAX_ESTATE, NETMAX_EDEVICE, NETMAX_ENOMEM = range(6)
 NETMAX_FLAT, NETMAX_MLP = 0, 1
 NETMAX_F32, NETMAX_BF16 = 0, 1
+NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
@@ -42,6 +43,7 @@ class netmax_config(C.Structure):
         ("grad_sigma", C.c_float),
         ("seed", C.c_uint64), ("strict_o3", C.c_int32),
         ("P", C.c_void_p), ("adj", C.c_void_p), ("stream", C.c_void_p),
+        ("mix_mode", C.c_int32), ("fixed_weight", C.c_float),
     ]
 
 
@@ -60,7 +62,7 @@ def load():
     vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
     sig = {
         "netmax_init": (C.c_int, [C.POINTER(vp), C.POINTER(netmax_config)]),
-        "netmax_build_tables": (C.c_int, [i32, vp, vp, f32, f32, i32, vp, vp, vp]),
+        "netmax_build_tables": (C.c_int, [i32, vp, vp, f32, f32, i32, i32, f32, vp, vp, vp]),
         "netmax_generate_policy": (C.c_int, [i32, vp, vp, C.c_double, i32, i32, C.c_double, vp, vp, vp, vp, vp]),
         "netmax_set_policy": (C.c_int, [vp, vp, f32]),
         "netmax_set_lr": (C.c_int, [vp, f32]),
@@ -116,14 +118,16 @@ def _dp(t, dtype=None):
 
 # ---- the C entry points, one Python function each -------------------------------------------------
 
-def netmax_build_tables(P: np.ndarray, adj: Optional[np.ndarray], lr: float, rho: float, strict_o3: bool = False):
+def netmax_build_tables(P: np.ndarray, adj: Optional[np.ndarray], lr: float, rho: float, strict_o3: bool = False,
+                        mix_mode: int = NETMAX_MIX_POLICY, fixed_weight: float = 0.5):
     P = _host(P, np.float64)
     M = P.shape[0]
     adj = _host(adj, np.uint8)
     thr = np.empty((M, M), np.uint32)
     last = np.empty(M, np.int32)
     w = np.empty((M, M), np.float32)
-    _check(load().netmax_build_tables(M, _hp(P), _hp(adj), lr, rho, int(strict_o3), _hp(thr), _hp(last), _hp(w)))
+    _check(load().netmax_build_tables(M, _hp(P), _hp(adj), lr, rho, int(strict_o3), mix_mode, fixed_weight, _hp(thr),
+                                      _hp(last), _hp(w)))
     return thr, last, w
 
 
@@ -145,7 +149,8 @@ def netmax_generate_policy(t: np.ndarray, alpha: float, K: int, R: int, adj: Opt
 def netmax_init(*, M: int, D: int, ld: int, model: int, dims: Sequence[int] = (), batch: int = 0,
                 gemm_in: int = NETMAX_F32, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
                 rho: float, grad_sigma: float = 0.0, seed: int, strict_o3: bool = False, P: np.ndarray,
-                adj: Optional[np.ndarray] = None, stream: int = 0):
+                adj: Optional[np.ndarray] = None, stream: int = 0, mix_mode: int = NETMAX_MIX_POLICY,
+                fixed_weight: float = 0.5):
     cfg = netmax_config()
     cfg.M, cfg.D, cfg.ld, cfg.model = M, D, ld, model
     cfg.n_layers = max(len(dims) - 1, 0)
@@ -159,6 +164,7 @@ def netmax_init(*, M: int, D: int, ld: int, model: int, dims: Sequence[int] = ()
     adj = _host(adj, np.uint8)
     cfg.P, cfg.adj = P.ctypes.data, (adj.ctypes.data if adj is not None else None)
     cfg.stream = stream
+    cfg.mix_mode, cfg.fixed_weight = mix_mode, fixed_weight
     ctx = C.c_void_p()
     _check(load().netmax_init(C.byref(ctx), C.byref(cfg)))
     return ctx
@@ -254,7 +260,7 @@ class NetMax:
 
     def __init__(self, *, M, D, ld, model, dims=(), batch=0, gemm_in=NETMAX_F32, lr, momentum=0.0,
                  weight_decay=0.0, rho, grad_sigma=0.0, seed, P, adj=None, strict_o3=False,
-                 X0: Optional[np.ndarray] = None, feats=None, labels=None, shard_off=None, device="cuda:0"):
+                 mix_mode=NETMAX_MIX_POLICY, fixed_weight=0.5, X0: Optional[np.ndarray] = None, feats=None, labels=None, shard_off=None, device="cuda:0"):
         import torch
         assert ld % NETMAX_TILE == 0, "ld must be a multiple of NETMAX_TILE"
         self.M, self.D, self.ld, self.batch = M, D, ld, batch
@@ -263,7 +269,8 @@ class NetMax:
         self.stream = torch.cuda.current_stream(self.device).cuda_stream
         self.ctx = netmax_init(M=M, D=D, ld=ld, model=model, dims=dims, batch=batch, gemm_in=gemm_in, lr=lr,
                                momentum=momentum, weight_decay=weight_decay, rho=rho, grad_sigma=grad_sigma,
-                               seed=seed, strict_o3=strict_o3, P=P, adj=adj, stream=self.stream)
+                               seed=seed, strict_o3=strict_o3, P=P, adj=adj, stream=self.stream, mix_mode=mix_mode,
+                               fixed_weight=fixed_weight)
         kw = dict(dtype=torch.float32, device=self.device)
         self.x_a = torch.zeros(M * ld, **kw)
         self.x_b = torch.zeros(M * ld, **kw)

@@ -71,15 +71,16 @@ static int fail(netmax_ctx *ctx, int code, const std::string &msg)
 // the row, scaled by 2^32 and rounded to nearest, with every position from the last positive entry on
 // forced to 2^32 (stored as 2^32 - 1 together with `last`, which the sampler clamps to).  Entries of
 // probability zero repeat the previous threshold and can never be drawn.
-// The second-step weight is w_im = alpha rho (d_im + d_mi) / (2 p_im) (Algorithm 2), 0 for m = i.
+// The second-step weight is w_im = alpha rho (d_im + d_mi) / (2 p_im) (Algorithm 2), 0 for m = i; in the
+// fixed-weight mode (gossip / AD-PSGD averaging under the same policy, Section III-D) it is one constant.
 static int build_tables(int M, const double *P, const uint8_t *adj, double alpha, double rho, bool strict,
-                        std::vector<uint32_t> &thr, std::vector<int32_t> &last, std::vector<float> &w,
+                        int mix_mode, double fixed_weight, std::vector<uint32_t> &thr, std::vector<int32_t> &last, std::vector<float> &w,
                         std::string &why)
 {
     thr.assign((size_t)M * M, 0u);
     last.assign(M, 0);
     w.assign((size_t)M * M, 0.0f);
-    const double limit = strict ? 0.5 : 1.0;
+    const double limit = (strict && mix_mode == NETMAX_MIX_POLICY) ? 0.5 : 1.0;   // (o3) concerns Algorithm 2's weights
     char buf[200];
     for (int i = 0; i < M; ++i) {
         const double *row = P + (size_t)i * M;
@@ -121,7 +122,7 @@ static int build_tables(int M, const double *P, const uint8_t *adj, double alpha
             thr[(size_t)i * M + m] = fixed > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)fixed;
             if (m != i && row[m] > 0.0) {
                 const double links = adj ? (double)((adj[(size_t)i * M + m] != 0) + (adj[(size_t)m * M + i] != 0)) : 2.0;
-                const double weight = alpha * rho * links / (2.0 * row[m]);
+                const double weight = mix_mode == NETMAX_MIX_FIXED ? fixed_weight : alpha * rho * links / (2.0 * row[m]);
                 if (!(weight < limit)) {
                     snprintf(buf, sizeof buf, "mix weight of pair (%d,%d) is %g, must be below %g%s", i, m, weight, limit,
                              strict ? " (constraint (o3))" : "");
@@ -152,7 +153,8 @@ static int rebuild_policy(netmax_ctx *ctx, const double *P, double alpha, double
     std::vector<float> w;
     std::string why;
     const int rc = build_tables(ctx->cfg.M, P, ctx->has_adj ? ctx->adj.data() : nullptr, alpha, rho,
-                                ctx->cfg.strict_o3 != 0, thr, last, w, why);
+                                ctx->cfg.strict_o3 != 0, ctx->cfg.mix_mode, (double)ctx->cfg.fixed_weight, thr, last, w,
+                                why);
     if (rc != NETMAX_OK) return fail(ctx, rc, why);
     // the stream may still read the old tables: wait before they are overwritten
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -202,6 +204,10 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
         return fail(nullptr, NETMAX_EINVAL, "need lr > 0, 0 <= momentum < 1, weight_decay >= 0, rho >= 0");
     if (cfg->model != NETMAX_FLAT && cfg->model != NETMAX_MLP) return fail(nullptr, NETMAX_EINVAL, "unknown model kind");
     if (cfg->gemm_in != NETMAX_F32 && cfg->gemm_in != NETMAX_BF16) return fail(nullptr, NETMAX_EINVAL, "unknown gemm_in");
+    if (cfg->mix_mode != NETMAX_MIX_POLICY && cfg->mix_mode != NETMAX_MIX_FIXED)
+        return fail(nullptr, NETMAX_EINVAL, "unknown mix_mode");
+    if (cfg->mix_mode == NETMAX_MIX_FIXED && (!(cfg->fixed_weight >= 0.0f) || !(cfg->fixed_weight < 1.0f)))
+        return fail(nullptr, NETMAX_EINVAL, "fixed_weight must be in [0, 1)");
 
     netmax_ctx *ctx = new (std::nothrow) netmax_ctx;
     if (!ctx) return fail(nullptr, NETMAX_ENOMEM, "out of host memory");
@@ -244,7 +250,8 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
     }
     std::string why;
     int rc = build_tables(M, ctx->P.data(), ctx->has_adj ? ctx->adj.data() : nullptr, (double)cfg->lr, (double)cfg->rho,
-                          cfg->strict_o3 != 0, ctx->h_thr, ctx->h_last, ctx->h_w, why);
+                          cfg->strict_o3 != 0, cfg->mix_mode, (double)cfg->fixed_weight, ctx->h_thr, ctx->h_last, ctx->h_w,
+                          why);
     if (rc != NETMAX_OK) {
         release(ctx);
         return fail(nullptr, rc, why);
@@ -303,15 +310,19 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
 }
 
 extern "C" int netmax_build_tables(int32_t M, const double *P, const uint8_t *adj, float lr, float rho, int32_t strict_o3,
-                                   uint32_t *thresholds_host, int32_t *last_host, float *w_host)
+                                   int32_t mix_mode, float fixed_weight, uint32_t *thresholds_host, int32_t *last_host,
+                                   float *w_host)
 {
-    if (M < 2 || M > 4096 || !P || !thresholds_host || !last_host || !w_host || !(lr > 0.0f) || !(rho >= 0.0f))
+    if (M < 2 || M > 4096 || !P || !thresholds_host || !last_host || !w_host || !(lr > 0.0f) || !(rho >= 0.0f) ||
+        (mix_mode != NETMAX_MIX_POLICY && mix_mode != NETMAX_MIX_FIXED) ||
+        (mix_mode == NETMAX_MIX_FIXED && (!(fixed_weight >= 0.0f) || !(fixed_weight < 1.0f))))
         return fail(nullptr, NETMAX_EINVAL, "bad argument");
     std::vector<uint32_t> thr;
     std::vector<int32_t> last;
     std::vector<float> w;
     std::string why;
-    const int rc = build_tables(M, P, adj, (double)lr, (double)rho, strict_o3 != 0, thr, last, w, why);
+    const int rc = build_tables(M, P, adj, (double)lr, (double)rho, strict_o3 != 0, mix_mode, (double)fixed_weight, thr,
+                                last, w, why);
     if (rc != NETMAX_OK) return fail(nullptr, rc, why);
     memcpy(thresholds_host, thr.data(), thr.size() * sizeof(uint32_t));
     memcpy(last_host, last.data(), last.size() * sizeof(int32_t));

@@ -17,23 +17,26 @@ def hyper(w: Workload, rho: float):
     return hyperparameters(w, rho)
 
 
-def make_gpu(w: Workload, inp, **over):
+def make_gpu(w: Workload, inp, fixed_weight=None, **over):
+    """fixed_weight: use the same second-step weight for every drawn pair (gossip / AD-PSGD averaging)."""
     import paper_2009_05766_amd as nm
     h = hyper(w, inp["rho"])
     h.update(over)
+    if fixed_weight is not None:
+        h.update(mix_mode=nm.NETMAX_MIX_FIXED, fixed_weight=fixed_weight)
     return nm.NetMax(M=w.M, D=w.D, ld=w.ld, model=nm.NETMAX_FLAT if w.model == "flat" else nm.NETMAX_MLP,
                      dims=w.dims, batch=w.batch, gemm_in=nm.NETMAX_BF16 if w.gemm_in == "bf16" else nm.NETMAX_F32,
                      seed=w.seed, P=inp["P"], X0=inp["X0"], feats=inp["feats"], labels=inp["labels"],
                      shard_off=inp["shard_off"], **h)
 
 
-def make_oracle(w: Workload, inp, operands_bf16=False, **over):
+def make_oracle(w: Workload, inp, operands_bf16=False, fixed_weight=None, **over):
     """operands_bf16: the oracle rounds the operands of every matrix product to bfloat16, as the bf16
     workload prescribes; False gives exact arithmetic."""
     import oracle
     h = hyper(w, inp["rho"])
     h.update(over)
-    return oracle.Oracle(operands_bf16=operands_bf16, M=w.M, ld=w.ld, D=w.D, dims=w.dims, batch=w.batch, seed=w.seed, P=inp["P"],
+    return oracle.Oracle(operands_bf16=operands_bf16, fixed_weight=fixed_weight, M=w.M, ld=w.ld, D=w.D, dims=w.dims, batch=w.batch, seed=w.seed, P=inp["P"],
                          X0=inp["X0"], feats=inp["feats"], labels=inp["labels"], shard_off=inp["shard_off"], **h)
 
 

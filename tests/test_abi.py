@@ -73,3 +73,15 @@ def test_host_table_errors():
     with pytest.raises(nm.NetmaxError) as e:     # positive probability on a non-edge, constraint (o4)
         nm.netmax_build_tables(P2, adj, 0.1, 0.001)
     assert e.value.code == nm.NETMAX_EINVAL
+
+
+def test_host_tables_fixed_weight_mode(ora):
+    w = workload("cfg2")
+    P, rho = policy_for(w)
+    thr, last, wt = nm.netmax_build_tables(P, None, 0.01, rho, strict_o3=True, mix_mode=nm.NETMAX_MIX_FIXED,
+                                           fixed_weight=0.5)
+    T, l = ora.thresholds(P)
+    assert np.array_equal(thr, T) and np.array_equal(last, l)
+    assert np.array_equal(wt, ora.mix_weights_fixed(P, 0.5).astype(np.float32))
+    with pytest.raises(nm.NetmaxError):
+        nm.netmax_build_tables(P, None, 0.01, rho, mix_mode=nm.NETMAX_MIX_FIXED, fixed_weight=1.0)

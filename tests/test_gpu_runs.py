@@ -266,3 +266,16 @@ def test_generated_policy_installed_mid_run():
         assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it))
     assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
     gpu.close()
+
+
+def test_fixed_weight_averaging_mode():
+    """Gossip / AD-PSGD averaging (weight 1/2 for every pulled model) under the link-speed-tuned policy."""
+    w = workload("cfg3", M=16, D=20000, T=40)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp, fixed_weight=0.5), make_oracle(w, inp, fixed_weight=0.5)
+    for it in range(w.T):
+        gpu.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it))
+    assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
+    assert gpu.consensus_dist() == pytest.approx(o.consensus_dist(), rel=1e-3)
+    gpu.close()

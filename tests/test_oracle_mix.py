@@ -204,3 +204,23 @@ def test_consensus_distance_equals_pair_sum(ora):
     pair = sum(np.sum((Xd[i] - Xd[m]) ** 2) for i in range(M) for m in range(M)) / (2 * M)
     assert ora.consensus_dist(X, D) == pytest.approx(pair, rel=1e-12)
     assert ora.consensus_dist(np.tile(X[0], (M, 1)), D) == 0.0
+
+
+def test_fixed_weight_one_half_is_plain_averaging(ora):
+    """The gossip / AD-PSGD variant (Section III-D): with weight 1/2 and no gradient two workers that pull from
+    each other both land on their mean after one step; the weight does not depend on the policy."""
+    rng = np.random.default_rng(11)
+    P = np.array([[0.0, 1.0], [1.0, 0.0]])
+    w = ora.mix_weights_fixed(P, 0.5)
+    assert w[0, 1] == 0.5 and w[1, 0] == 0.5 and w[0, 0] == 0 and w[1, 1] == 0
+    X = rng.standard_normal((2, 64)).astype(np.float32)
+    out = ora.mix(X, np.zeros_like(X), np.zeros_like(X), np.array([1, 0], np.int32), w, 0.1, 0.0, 0.0)
+    mean = X.astype(np.float64).mean(0)
+    np.testing.assert_allclose(out[0], mean, atol=1e-7)
+    np.testing.assert_allclose(out[1], mean, atol=1e-7)
+    assert ora.consensus_dist(out) < 1e-12
+    P3 = _policy(rng, 5)
+    P3[0, 2] = 0.0
+    P3 /= P3.sum(1, keepdims=True)
+    w3 = ora.mix_weights_fixed(P3, 0.3)
+    assert w3[0, 2] == 0 and np.all(np.diag(w3) == 0) and set(np.unique(w3)) == {0.0, 0.3}
