@@ -82,6 +82,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3", help="cfg1..cfg5 (default: cfg3, the HBM-bound ResNet18-sized mix)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", choices=("calls", "run", "graph"), default="calls",
+                    help="calls: the three entry points per step, events around each phase (default); run: one "
+                         "netmax_run call for all steps; graph: netmax_run replaying captured HIP graphs")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="before the timed region, run this many plain device copies of the parameter matrix "
                          "(a kernel of known traffic, used to scale profiler byte counters)")
@@ -106,6 +109,8 @@ def main() -> int:
     inp = dict(P=P, rho=rho, feats=feats, labels=labels, shard_off=shard_off, X0=X0)
     print(f"[bench] inputs of {w.name} generated in {time.perf_counter() - t_in:.1f} s", file=sys.stderr, flush=True)
 
+    side = torch.cuda.Stream()          # default priority; a real stream, so that iterations can be captured
+    torch.cuda.set_stream(side)
     gpu = nm.NetMax(M=w.M, D=w.D, ld=w.ld, model=nm.NETMAX_FLAT if w.model == "flat" else nm.NETMAX_MLP, dims=w.dims,
                     batch=w.batch, gemm_in=nm.NETMAX_BF16 if w.gemm_in == "bf16" else nm.NETMAX_F32, seed=w.seed, P=P,
                     X0=X0, feats=feats, labels=labels, shard_off=shard_off, **hyper(w, rho))
@@ -121,10 +126,11 @@ def main() -> int:
     torch.cuda.synchronize()
 
     K = args.steps
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    K_ev = K if args.mode == "calls" else min(K, 50)      # phase timing: events around every entry point
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K_ev)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(K):
+    for k in range(K_ev):
         it = args.warmup + k
         e = ev[k]
         e[0].record()
@@ -136,6 +142,14 @@ def main() -> int:
         e[3].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if args.mode != "calls":
+        first = args.warmup + K_ev
+        gpu.run(first, 4, use_graph=args.mode == "graph")          # captures both directions outside the timed region
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        gpu.run(first + 4, K, use_graph=args.mode == "graph")
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
 
     ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in ev])   # sample, grad, mix
     ms_sample, ms_grad, ms_mix = ms.mean(axis=0)
@@ -156,7 +170,8 @@ def main() -> int:
     out = {"metric": "worker-iterations/sec (sample+grad+mix)", "value": value, "unit": "worker-iterations/s",
            "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_in == "bf16" else "f32",
-           "data": "synthetic", "config": {"workload": describe(w), "M": w.M, "D": w.D, "iterations": K},
+           "data": "synthetic", "config": {"workload": describe(w), "M": w.M, "D": w.D, "iterations": K,
+                                           "launch": args.mode},
            "phase_ms": {"sample_peers": float(ms_sample), "local_step": float(ms_grad), "mix": float(ms_mix)},
            "consensus_distance": {"before": cd0, "after": cd1},
            "roofline": roofline}

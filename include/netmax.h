@@ -161,6 +161,15 @@ int netmax_local_step(netmax_ctx *ctx, uint64_t iter);
  * parameter buffers.  `iter` is recorded for netmax_iteration(). */
 int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev);
 
+/* n_iters whole iterations (netmax_sample_peers, netmax_local_step, netmax_mix for iter = first_iter, first_iter + 1,
+ * ...) enqueued from one call; peers_dev (device int32 [M]) receives each iteration's peers in turn.  With
+ * use_graph != 0 an iteration is recorded once per direction of the parameter ping-pong into a HIP graph and
+ * replayed (the iteration number then lives in a device cell that the graph advances), which removes the launch
+ * overhead that dominates small models; this needs a context created on a non-default stream (the null stream
+ * cannot be captured), else NETMAX_ESTATE.  The graphs are dropped when buffers, data or the learning rate change.
+ * Results are identical to the individual calls. */
+int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *peers_dev, int32_t use_graph);
+
 /* Consensus distance sum_i ||x_i - mean_i x_i||^2 over the first D columns of the current parameters: the
  * complete-graph form of the model-difference penalty of Eq. (1).  fp64 accumulation, fixed summation
  * order.  Waits for the stream; out_host: host double. */

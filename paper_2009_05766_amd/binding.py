@@ -22,7 +22,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run",
     "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -74,6 +74,7 @@ def load():
         "netmax_sample_batch": (C.c_int, [vp, u64, vp]),
         "netmax_local_step": (C.c_int, [vp, u64]),
         "netmax_mix": (C.c_int, [vp, u64, vp]),
+        "netmax_run": (C.c_int, [vp, u64, i32, vp, i32]),
         "netmax_consensus_dist": (C.c_int, [vp, C.POINTER(C.c_double)]),
         "netmax_params": (vp, [vp]),
         "netmax_losses": (vp, [vp]),
@@ -220,6 +221,11 @@ def netmax_mix(ctx, it: int, peers):
     _check(load().netmax_mix(ctx, it, _dp(peers, torch.int32)), ctx)
 
 
+def netmax_run(ctx, first_iter: int, n_iters: int, peers, use_graph: bool = False):
+    import torch
+    _check(load().netmax_run(ctx, first_iter, n_iters, _dp(peers, torch.int32), int(use_graph)), ctx)
+
+
 def netmax_consensus_dist(ctx) -> float:
     out = C.c_double()
     _check(load().netmax_consensus_dist(ctx, C.byref(out)), ctx)
@@ -338,6 +344,9 @@ class NetMax:
         netmax_sample_peers(self.ctx, it, self.peers)
         netmax_local_step(self.ctx, it)
         netmax_mix(self.ctx, it, self.peers)
+
+    def run(self, first_iter: int, n_iters: int, use_graph: bool = False):
+        netmax_run(self.ctx, first_iter, n_iters, self.peers, use_graph)
 
     def consensus_dist(self) -> float:
         return netmax_consensus_dist(self.ctx)

@@ -596,6 +596,13 @@ bool mfma_small_last_ok(const MlpPlan &p)
     return p.bf16 && l > 0 && dout <= 32 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && din <= SMALL_MAX_DIN;
 }
 
+void prepare_kernels()
+{
+    // fwd_small_mfma_kernel keeps W^T in more than the default 64 KB of dynamic LDS
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_small_mfma_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 32 * (SMALL_MAX_DIN + 8) * 2);
+}
+
 void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X)
 {
     const int l = p.n_layers - 1;
@@ -603,12 +610,6 @@ void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X)
     a.a_prev = p.hb[l]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.out = p.act[l + 1];
     const size_t lds = (size_t)32 * (a.din + 8) * sizeof(uint16_t);
-    static bool raised = false;
-    if (!raised) {   // more than the default 64 KB of dynamic LDS
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_small_mfma_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 32 * (SMALL_MAX_DIN + 8) * 2);
-        raised = true;
-    }
     hipLaunchKernelGGL(fwd_small_mfma_kernel, dim3(p.M), dim3(MF_THREADS), lds, s, a);
 }
 

@@ -9,10 +9,11 @@ namespace netmax {
 // number of thresholds <= u (the first m whose threshold exceeds u), clamped to the last positive entry.
 __global__ void __launch_bounds__(256) sample_peers_kernel(int M, const uint32_t *__restrict__ thr,
                                                            const int32_t *__restrict__ last, uint64_t seed,
-                                                           uint64_t iter, int32_t *__restrict__ peer)
+                                                           IterRef iter_ref, int32_t *__restrict__ peer)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= M) return;
+    const uint64_t iter = iteration_of(iter_ref);
     const uint32_t u = draw_block(seed, STREAM_PEER, 0u, (uint32_t)i, iter).a;
     const uint32_t *row = thr + (size_t)i * M;
     int lo = 0, hi = M;  // upper bound: first position with row[pos] > u
@@ -26,11 +27,12 @@ __global__ void __launch_bounds__(256) sample_peers_kernel(int M, const uint32_t
 
 // One thread per Philox block of four draws: idx[i][4q..4q+3] = floor(word * n_i / 2^32).
 __global__ void __launch_bounds__(256) sample_batch_kernel(int M, int B, const int32_t *__restrict__ n_rows,
-                                                           uint64_t seed, uint64_t iter, int32_t *__restrict__ idx)
+                                                           uint64_t seed, IterRef iter_ref, int32_t *__restrict__ idx)
 {
     const int quads = (B + 3) >> 2;
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= M * quads) return;
+    const uint64_t iter = iteration_of(iter_ref);
     const int i = t / quads, q = t - i * quads;
     const Words4 r = draw_block(seed, STREAM_BATCH, (uint32_t)q, (uint32_t)i, iter);
     const uint32_t n = (uint32_t)n_rows[i];
@@ -43,16 +45,28 @@ __global__ void __launch_bounds__(256) sample_batch_kernel(int M, int B, const i
 }
 
 void launch_sample_peers(hipStream_t s, int M, const uint32_t *thr, const int32_t *last, uint64_t seed,
-                         uint64_t iter, int32_t *peer)
+                         const IterRef &iter, int32_t *peer)
 {
     hipLaunchKernelGGL(sample_peers_kernel, dim3((M + 255) / 256), dim3(256), 0, s, M, thr, last, seed, iter, peer);
 }
 
-void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uint64_t seed, uint64_t iter,
+void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uint64_t seed, const IterRef &iter,
                          int32_t *idx)
 {
     const int n = M * ((B + 3) / 4);
     hipLaunchKernelGGL(sample_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, s, M, B, n_rows, seed, iter, idx);
+}
+
+__global__ void set_iteration_kernel(uint64_t *cell, uint64_t value) { *cell = value; }
+__global__ void bump_iteration_kernel(uint64_t *cell) { *cell += 1; }
+
+void launch_set_iteration(hipStream_t s, uint64_t *cell, uint64_t value)
+{
+    hipLaunchKernelGGL(set_iteration_kernel, dim3(1), dim3(1), 0, s, cell, value);
+}
+void launch_bump_iteration(hipStream_t s, uint64_t *cell)
+{
+    hipLaunchKernelGGL(bump_iteration_kernel, dim3(1), dim3(1), 0, s, cell);
 }
 
 }  // namespace netmax

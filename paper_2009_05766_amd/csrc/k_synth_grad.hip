@@ -29,8 +29,9 @@ __device__ __forceinline__ void box_muller(uint32_t w0, uint32_t w1, float &z0, 
 // grid.x = 2 M: workgroup (worker, half tile); grid.y strides over the column tiles, so consecutive
 // workgroups write consecutive 4 KB pieces of G and no thread needs a division.
 __global__ void __launch_bounds__(256) synth_grad_kernel(int M, int64_t D, int64_t n_tiles, float sigma, uint64_t seed,
-                                                         uint64_t iter, float *__restrict__ G)
+                                                         IterRef iter_ref, float *__restrict__ G)
 {
+    const uint64_t iter = iteration_of(iter_ref);
     const uint32_t i = blockIdx.x >> 1;
     const int q = (int)(blockIdx.x & 1) * 256 + (int)threadIdx.x;            // quad inside the tile
     for (int64_t tile = blockIdx.y; tile < n_tiles; tile += gridDim.y) {
@@ -48,7 +49,7 @@ __global__ void __launch_bounds__(256) synth_grad_kernel(int M, int64_t D, int64
     }
 }
 
-void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, uint64_t iter,
+void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, const IterRef &iter,
                        float *G)
 {
     static_assert(TILE == 2048, "two workgroups of 256 threads x 4 columns cover one tile");

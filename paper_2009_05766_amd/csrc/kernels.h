@@ -6,17 +6,26 @@
 
 namespace netmax {
 
+struct IterRef;   // philox.h: iteration number by value or from a device cell
+
 // Peer selection of Algorithm 2: one Philox draw per worker against fixed-point cumulative thresholds.
 void launch_sample_peers(hipStream_t s, int M, const uint32_t *thr, const int32_t *last, uint64_t seed,
-                         uint64_t iter, int32_t *peer);
+                         const IterRef &iter, int32_t *peer);
 
 // Batch draws (with replacement) for every worker; n_rows[i] = shard size of worker i.
-void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uint64_t seed, uint64_t iter,
+void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uint64_t seed, const IterRef &iter,
                          int32_t *idx);
 
 // g[i][j] = sigma * N(0,1) from Philox + Box-Muller; padding columns are zeroed.
-void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, uint64_t iter,
+void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, const IterRef &iter,
                        float *G);
+
+// The device cell of the iteration number used by graph replays: set it, advance it by one.
+void launch_set_iteration(hipStream_t s, uint64_t *cell, uint64_t value);
+void launch_bump_iteration(hipStream_t s, uint64_t *cell);
+
+// One-time kernel attributes (LDS limits); call once per process before the first launch.
+void prepare_kernels();
 
 // Momentum apply + mix, Eq. (c0)/(c1), for all workers.
 void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float *G, float *V, float *Xnext,

@@ -3,6 +3,7 @@
 #include "../../include/netmax.h"
 #include "kernels.h"
 #include "layout.h"
+#include "philox.h"
 
 #include <cmath>
 #include <cstdio>
@@ -47,6 +48,11 @@ struct netmax_ctx {
     // consensus distance
     double *d_partial = nullptr, *d_cd = nullptr;
     uint64_t iterations = 0;
+    // graph replay (netmax_run): one captured iteration per direction of the parameter ping-pong
+    float *x_first = nullptr;                 // the buffer bound as x_a: decides which graph an iteration uses
+    uint64_t *d_iter = nullptr;               // device cell holding the iteration number of the next replay
+    hipGraphExec_t graph_exec[2] = {nullptr, nullptr};
+    const int32_t *graph_peers = nullptr;
     std::string err;
 };
 
@@ -164,8 +170,19 @@ static int rebuild_policy(netmax_ctx *ctx, const double *P, double alpha, double
     return upload_tables(ctx);
 }
 
+static void drop_graphs(netmax_ctx *ctx)
+{
+    for (auto &g : ctx->graph_exec) {
+        if (g) (void)hipGraphExecDestroy(g);
+        g = nullptr;
+    }
+    ctx->graph_peers = nullptr;
+}
+
 static void release(netmax_ctx *ctx)
 {
+    drop_graphs(ctx);
+    (void)hipFree(ctx->d_iter);
     (void)hipFree(ctx->d_thr); (void)hipFree(ctx->d_last); (void)hipFree(ctx->d_w);
     (void)hipFree(ctx->d_row0); (void)hipFree(ctx->d_nrows); (void)hipFree(ctx->d_idx);
     for (auto *p : ctx->d_act) (void)hipFree(p);
@@ -273,6 +290,8 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
     INIT_TRY(hipMalloc(&ctx->d_w, mm * sizeof(float)));
     INIT_TRY(hipMalloc(&ctx->d_partial, (size_t)consensus_partials(cfg->ld) * sizeof(double)));
     INIT_TRY(hipMalloc(&ctx->d_cd, sizeof(double)));
+    INIT_TRY(hipMalloc(&ctx->d_iter, sizeof(uint64_t)));
+    prepare_kernels();
     if (cfg->model == NETMAX_MLP) {
         const size_t MB = (size_t)M * cfg->batch;
         int64_t widest = 0;
@@ -358,6 +377,7 @@ extern "C" int netmax_set_lr(netmax_ctx *ctx, float lr)
     const int rc = rebuild_policy(ctx, ctx->P.data(), (double)lr, (double)ctx->cfg.rho);
     if (rc != NETMAX_OK) return rc;
     ctx->cfg.lr = lr;
+    drop_graphs(ctx);                          // alpha is an argument of the captured mix kernel
     return NETMAX_OK;
 }
 
@@ -368,7 +388,9 @@ extern "C" int netmax_bind_state(netmax_ctx *ctx, float *x_a, float *x_b, float 
     if (x_a == x_b) return fail(ctx, NETMAX_EINVAL, "x_a and x_b must be different buffers");
     for (const void *p : {(const void *)x_a, (const void *)x_b, (const void *)v, (const void *)g})
         if ((uintptr_t)p % 16 != 0) return fail(ctx, NETMAX_EINVAL, "state pointers must be 16-byte aligned");
-    ctx->x_cur = x_a;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    drop_graphs(ctx);
+    ctx->x_cur = ctx->x_first = x_a;
     ctx->x_next = x_b;
     ctx->v = v;
     ctx->g = g;
@@ -412,6 +434,7 @@ extern "C" int netmax_bind_data(netmax_ctx *ctx, const void *feats, const int32_
     HIP_TRY(ctx, hipMemcpyAsync(&flag, ctx->d_flag, sizeof flag, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     if (flag) return fail(ctx, NETMAX_EINVAL, "a label is outside [0, number of classes)");
+    drop_graphs(ctx);
     ctx->feats = feats;
     ctx->labels = labels;
     ctx->data_bound = true;
@@ -434,33 +457,20 @@ extern "C" int netmax_unpack(netmax_ctx *ctx, const float *tiled_dev, float *row
     return check_launch(ctx, "unpack");
 }
 
-extern "C" int netmax_sample_peers(netmax_ctx *ctx, uint64_t iter, int32_t *peers_dev)
+// The three phases of one iteration, enqueued on the context's stream (no argument checks, no pointer flip).
+static int enqueue_sample_peers(netmax_ctx *ctx, const IterRef &iter, int32_t *peers_dev)
 {
-    if (!ctx) return NETMAX_EINVAL;
-    if (!peers_dev) return fail(ctx, NETMAX_EINVAL, "peers_dev is NULL");
     launch_sample_peers(ctx->stream, ctx->cfg.M, ctx->d_thr, ctx->d_last, ctx->cfg.seed, iter, peers_dev);
     return check_launch(ctx, "sample_peers");
 }
 
-extern "C" int netmax_sample_batch(netmax_ctx *ctx, uint64_t iter, int32_t *idx_dev)
+static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter)
 {
-    if (!ctx) return NETMAX_EINVAL;
-    if (ctx->cfg.model != NETMAX_MLP || !ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
-    if (!idx_dev) return fail(ctx, NETMAX_EINVAL, "idx_dev is NULL");
-    launch_sample_batch(ctx->stream, ctx->cfg.M, ctx->cfg.batch, ctx->d_nrows, ctx->cfg.seed, iter, idx_dev);
-    return check_launch(ctx, "sample_batch");
-}
-
-extern "C" int netmax_local_step(netmax_ctx *ctx, uint64_t iter)
-{
-    if (!ctx) return NETMAX_EINVAL;
-    if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
     const netmax_config &c = ctx->cfg;
     if (c.model == NETMAX_FLAT) {
         launch_synth_grad(ctx->stream, c.M, c.D, c.ld, c.grad_sigma, c.seed, iter, ctx->g);
         return check_launch(ctx, "synth_grad");
     }
-    if (!ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
     launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
     MlpPlan p{};
     p.M = c.M; p.n_layers = c.n_layers; p.B = c.batch; p.ld = c.ld; p.bf16 = (c.gemm_in == NETMAX_BF16);
@@ -475,21 +485,120 @@ extern "C" int netmax_local_step(netmax_ctx *ctx, uint64_t iter)
     return check_launch(ctx, "mlp_grad");
 }
 
+static int enqueue_mix(netmax_ctx *ctx, const int32_t *peers_dev)
+{
+    const netmax_config &c = ctx->cfg;
+    launch_mix(ctx->stream, c.M, c.ld, ctx->x_cur, ctx->g, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum,
+               c.weight_decay);
+    return check_launch(ctx, "mix");
+}
+
+static void flip(netmax_ctx *ctx)
+{
+    float *t = ctx->x_cur;
+    ctx->x_cur = ctx->x_next;
+    ctx->x_next = t;
+    ctx->iterations += 1;
+}
+
+extern "C" int netmax_sample_peers(netmax_ctx *ctx, uint64_t iter, int32_t *peers_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!peers_dev) return fail(ctx, NETMAX_EINVAL, "peers_dev is NULL");
+    return enqueue_sample_peers(ctx, IterRef{iter, nullptr}, peers_dev);
+}
+
+extern "C" int netmax_sample_batch(netmax_ctx *ctx, uint64_t iter, int32_t *idx_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (ctx->cfg.model != NETMAX_MLP || !ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
+    if (!idx_dev) return fail(ctx, NETMAX_EINVAL, "idx_dev is NULL");
+    launch_sample_batch(ctx->stream, ctx->cfg.M, ctx->cfg.batch, ctx->d_nrows, ctx->cfg.seed, IterRef{iter, nullptr}, idx_dev);
+    return check_launch(ctx, "sample_batch");
+}
+
+extern "C" int netmax_local_step(netmax_ctx *ctx, uint64_t iter)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
+    if (ctx->cfg.model == NETMAX_MLP && !ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
+    return enqueue_local_step(ctx, IterRef{iter, nullptr});
+}
+
 extern "C" int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev)
 {
     if (!ctx) return NETMAX_EINVAL;
     if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
     if (!peers_dev) return fail(ctx, NETMAX_EINVAL, "peers_dev is NULL");
     (void)iter;
-    const netmax_config &c = ctx->cfg;
-    launch_mix(ctx->stream, c.M, c.ld, ctx->x_cur, ctx->g, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum,
-               c.weight_decay);
-    const int rc = check_launch(ctx, "mix");
+    const int rc = enqueue_mix(ctx, peers_dev);
     if (rc != NETMAX_OK) return rc;
-    float *t = ctx->x_cur;
-    ctx->x_cur = ctx->x_next;
-    ctx->x_next = t;
-    ctx->iterations += 1;
+    flip(ctx);
+    return NETMAX_OK;
+}
+
+// One iteration (sample, local step, mix, advance the iteration cell) recorded into a HIP graph for the
+// current direction of the parameter ping-pong.  Every kernel argument is fixed: the iteration number is read
+// from the device cell.
+static int capture_iteration(netmax_ctx *ctx, int dir, int32_t *peers_dev)
+{
+    hipGraph_t graph = nullptr;
+    HIP_TRY(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
+    const IterRef it{0, ctx->d_iter};
+    int rc = enqueue_sample_peers(ctx, it, peers_dev);
+    if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it);
+    if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev);
+    if (rc == NETMAX_OK) {
+        launch_bump_iteration(ctx->stream, ctx->d_iter);
+        rc = check_launch(ctx, "bump_iteration");
+    }
+    const hipError_t e = hipStreamEndCapture(ctx->stream, &graph);
+    if (rc != NETMAX_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (e != hipSuccess) return fail(ctx, NETMAX_EDEVICE, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    const hipError_t ei = hipGraphInstantiate(&ctx->graph_exec[dir], graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (ei != hipSuccess) {
+        ctx->graph_exec[dir] = nullptr;
+        return fail(ctx, NETMAX_EDEVICE, std::string("hipGraphInstantiate: ") + hipGetErrorString(ei));
+    }
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *peers_dev, int32_t use_graph)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
+    if (ctx->cfg.model == NETMAX_MLP && !ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
+    if (!peers_dev || n_iters < 0) return fail(ctx, NETMAX_EINVAL, "peers_dev is NULL or n_iters < 0");
+    if (!use_graph) {
+        for (int32_t k = 0; k < n_iters; ++k) {
+            const IterRef it{first_iter + (uint64_t)k, nullptr};
+            int rc = enqueue_sample_peers(ctx, it, peers_dev);
+            if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it);
+            if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev);
+            if (rc != NETMAX_OK) return rc;
+            flip(ctx);
+        }
+        return NETMAX_OK;
+    }
+    if (!ctx->stream) return fail(ctx, NETMAX_ESTATE, "graph replay needs a non-default stream (the null stream cannot be captured)");
+    if (ctx->graph_peers != peers_dev) drop_graphs(ctx);
+    launch_set_iteration(ctx->stream, ctx->d_iter, first_iter);
+    int rc = check_launch(ctx, "set_iteration");
+    if (rc != NETMAX_OK) return rc;
+    for (int32_t k = 0; k < n_iters; ++k) {
+        const int dir = ctx->x_cur == ctx->x_first ? 0 : 1;
+        if (!ctx->graph_exec[dir]) {
+            rc = capture_iteration(ctx, dir, peers_dev);
+            if (rc != NETMAX_OK) return rc;
+            ctx->graph_peers = peers_dev;
+        }
+        HIP_TRY(ctx, hipGraphLaunch(ctx->graph_exec[dir], ctx->stream));
+        flip(ctx);
+    }
     return NETMAX_OK;
 }
 

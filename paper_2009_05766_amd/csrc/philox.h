@@ -25,6 +25,14 @@ __device__ __forceinline__ Words4 philox4x32_10(uint32_t c0, uint32_t c1, uint32
     return Words4{c0, c1, c2, c3};
 }
 
+// The iteration number of a draw: a value passed with the launch, or (cell != nullptr) a device cell that a
+// replayed HIP graph advances itself, so that the graph's kernel arguments never change.
+struct IterRef {
+    uint64_t value;
+    const uint64_t *cell;
+};
+__device__ __forceinline__ uint64_t iteration_of(IterRef r) { return r.cell ? *r.cell : r.value; }
+
 // The library's draws: key = (seed_lo, seed_hi ^ stream), counter = (block, worker, iter_lo, iter_hi).
 enum : uint32_t { STREAM_PEER = 0u, STREAM_BATCH = 1u, STREAM_GRAD = 2u };
 

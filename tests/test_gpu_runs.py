@@ -279,3 +279,54 @@ def test_fixed_weight_averaging_mode():
     assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
     assert gpu.consensus_dist() == pytest.approx(o.consensus_dist(), rel=1e-3)
     gpu.close()
+
+
+@pytest.mark.parametrize("name,over", [("cfg1", dict()), ("cfg3", dict(M=16, D=50000)),
+                                       ("cfg5", dict(M=4, n_per_worker=128, dims=(256, 128, 128, 10), batch=64)),
+                                       ("cfg2", dict(M=4, n_per_worker=256, dims=(96, 64, 10)))])
+def test_graph_replay_matches_the_individual_calls(name, over):
+    """netmax_run with HIP graph replay: several replays of both ping-pong directions, with eager work of
+    the same context and synchronisations in between; every replay is compared with the eager path bit for bit."""
+    import paper_2009_05766_amd as nm
+    w = workload(name, **over)
+    inp = inputs_of(w)
+    eager = make_gpu(w, inp)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = make_gpu(w, inp)
+        it = 0
+        for n in (3, 1, 4, 2, 5):
+            graph.run(it, n, use_graph=True)
+            side.synchronize()
+            for k in range(n):
+                eager.step(it + k)
+            torch.cuda.synchronize()
+            it += n
+            assert nm.netmax_iteration(graph.ctx) == it
+            assert np.array_equal(graph.peers.cpu().numpy(), eager.peers.cpu().numpy())
+            assert np.array_equal(graph.get("x").cpu().numpy(), eager.get("x").cpu().numpy()), (it, n)
+            assert np.array_equal(graph.get("v").cpu().numpy(), eager.get("v").cpu().numpy())
+            assert graph.consensus_dist() == eager.consensus_dist()          # eager work between replays
+        # the un-captured multi-iteration path gives the same again
+        graph.run(it, 3, use_graph=False)
+        for k in range(3):
+            eager.step(it + k)
+        side.synchronize()
+        torch.cuda.synchronize()
+        assert np.array_equal(graph.get("x").cpu().numpy(), eager.get("x").cpu().numpy())
+        # a new learning rate drops the captured graphs; the next replay uses it
+        lr2 = float(np.float32(w.lr * 0.5))
+        nm.netmax_set_lr(graph.ctx, lr2)
+        nm.netmax_set_lr(eager.ctx, lr2)
+        graph.run(it + 3, 2, use_graph=True)
+        for k in range(2):
+            eager.step(it + 3 + k)
+        side.synchronize()
+        torch.cuda.synchronize()
+        assert np.array_equal(graph.get("x").cpu().numpy(), eager.get("x").cpu().numpy())
+        graph.close()
+    # the null stream cannot be captured: a clear error instead
+    with pytest.raises(nm.NetmaxError) as e:
+        eager.run(100, 1, use_graph=True)
+    assert e.value.code == nm.NETMAX_ESTATE
+    eager.close()
