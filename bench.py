@@ -24,10 +24,14 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # its own, so the minimum HBM traffic counts x once: 5 * 4 = 20 B.  (Counting the peer read too gives 24 B.)
 MIX_BYTES_MIN, MIX_BYTES_NAIVE = 20, 24
 
-# HBM bytes per mix launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/mix_kernel_<workload>.md), each
+# HBM bytes per mix launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/mix_kernel_cfg3.md, mix_kernel_cfg4.md,
+# iteration_cfg5.md), each
 # counter scaled by what it reads for a plain device copy of known size.  Valid only for the kernel sources they
 # were taken with: keyed by the sha256 prefix of k_mix.hip + layout.h + vec.h, reported as null otherwise.
-MEASURED_TRAFFIC = {"cfg3": {"sources": "23936c2060ea38f1.3f97687d5424e9a2.f872db49a5d92e6f", "bytes": 14337775863}}
+_MIX_SOURCES = "23936c2060ea38f1.3f97687d5424e9a2.f872db49a5d92e6f"
+MEASURED_TRAFFIC = {"cfg3": {"sources": _MIX_SOURCES, "bytes": 14337682647},
+                    "cfg4": {"sources": _MIX_SOURCES, "bytes": 12800500944},
+                    "cfg5": {"sources": _MIX_SOURCES, "bytes": 10777033072}}
 
 
 def mix_sources_digest() -> str:
