@@ -10,7 +10,8 @@
 
 namespace netmax {
 
-constexpr int TM = 64, TN = 64, TK = 16, GEMM_THREADS = 256;
+constexpr int TM = 64, TN = 64, TK = 32, GEMM_THREADS = 256;
+constexpr int MAX_BATCH = 1024;
 
 // Input of layer l for worker g, batch row r, feature k: the gathered data row for l = 0, else the
 // previous layer's activation (fp32, or its stored bfloat16 copy when the operands are bf16).
@@ -18,10 +19,11 @@ struct LayerInput {
     const void *feats; int feats_bf16; const int64_t *row0; const int32_t *idx; const float *act_prev;
     const uint16_t *act_prev_bf16;
     int B; int64_t din; int first; int round;
-    __device__ __forceinline__ float at(int g, int r, int64_t k) const
+    // rows: the worker's batch as absolute data rows (row0[g] + idx[g][b]), staged in LDS by the kernel
+    __device__ __forceinline__ float at(int g, int r, int64_t k, const int64_t *rows) const
     {
         if (first) {
-            const int64_t row = row0[g] + idx[(size_t)g * B + r];
+            const int64_t row = rows[r];
             return feats_bf16 ? bf16_bits_to_float(((const uint16_t *)feats)[row * din + k])
                               : (round ? round_bf16(((const float *)feats)[row * din + k])
                                        : ((const float *)feats)[row * din + k]);
@@ -40,7 +42,9 @@ struct FwdProblem {
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return din; }
-    __device__ float a(int g, int64_t r, int64_t k) const { return in.at(g, (int)r, k); }
+    __device__ bool gathers() const { return in.first != 0; }
+    __device__ const LayerInput &input() const { return in; }
+    __device__ float a(int g, int64_t r, int64_t k, const int64_t *rows) const { return in.at(g, (int)r, k, rows); }
     __device__ float b(int g, int64_t k, int64_t c) const
     {
         const float w = X[tiled_offset(M, g, woff + k * dout + c)];
@@ -67,7 +71,9 @@ struct DgradProblem {
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return din; }
     __device__ int64_t depth() const { return dout; }
-    __device__ float a(int g, int64_t r, int64_t k) const
+    __device__ bool gathers() const { return false; }
+    __device__ LayerInput input() const { return LayerInput{}; }
+    __device__ float a(int g, int64_t r, int64_t k, const int64_t *) const
     {
         const float d = dz[((size_t)g * B + r) * dout + k];
         return round ? round_bf16(d) : d;
@@ -98,7 +104,9 @@ struct WgradProblem {
     __device__ int64_t rows() const { return din; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return B; }
-    __device__ float a(int g, int64_t r, int64_t k) const { return in.at(g, (int)k, r); }
+    __device__ bool gathers() const { return in.first != 0; }
+    __device__ const LayerInput &input() const { return in; }
+    __device__ float a(int g, int64_t r, int64_t k, const int64_t *rows) const { return in.at(g, (int)k, r, rows); }
     __device__ float b(int g, int64_t k, int64_t c) const
     {
         const float d = dz[((size_t)g * B + k) * dout + c];
@@ -110,33 +118,62 @@ struct WgradProblem {
     }
 };
 
-// 64 x 64 output tile per workgroup, 4 x 4 per thread, K in steps of 16 through LDS.
+// 64 x 64 output tile per workgroup, 4 x 4 per thread, K in steps of 32 through LDS.  The operands of the
+// next step are fetched into registers while the current step is multiplied; the worker's batch rows are
+// resolved once into LDS, so no load in the loop depends on another.
 template <class Problem>
 __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
 {
     __shared__ float As[TK][TM + 4];
     __shared__ float Bs[TK][TN + 4];
+    __shared__ int64_t s_rows[MAX_BATCH];
     const int g = blockIdx.z, tid = threadIdx.x;
     const int64_t row0 = (int64_t)blockIdx.y * TM, col0 = (int64_t)blockIdx.x * TN;
     const int64_t R = p.rows(), C = p.cols(), K = p.depth();
     const int ty = tid / 16, tx = tid % 16;
-    float acc[4][4] = {};
-    for (int64_t k0 = 0; k0 < K; k0 += TK) {
+    if (p.gathers()) {
+        const LayerInput in = p.input();
+        for (int b = tid; b < in.B; b += GEMM_THREADS) s_rows[b] = in.row0[g] + in.idx[(size_t)g * in.B + b];
+        __syncthreads();
+    }
+    constexpr int A_PER = (TM * TK) / GEMM_THREADS, B_PER = (TN * TK) / GEMM_THREADS;
+    float ra[A_PER], rb[B_PER];
+    auto fetch = [&](int64_t k0) {
 #pragma unroll
-        for (int q = 0; q < (TM * TK) / GEMM_THREADS; ++q) {
+        for (int q = 0; q < A_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
             int kk, r;
             if (Problem::A_K_FAST) { kk = e % TK; r = e / TK; } else { r = e % TM; kk = e / TM; }
-            As[kk][r] = (row0 + r < R && k0 + kk < K) ? p.a(g, row0 + r, k0 + kk) : 0.0f;
+            ra[q] = (row0 + r < R && k0 + kk < K) ? p.a(g, row0 + r, k0 + kk, s_rows) : 0.0f;
         }
 #pragma unroll
-        for (int q = 0; q < (TN * TK) / GEMM_THREADS; ++q) {
+        for (int q = 0; q < B_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
             int kk, c;
             if (Problem::B_C_FAST) { c = e % TN; kk = e / TN; } else { kk = e % TK; c = e / TK; }
-            Bs[kk][c] = (col0 + c < C && k0 + kk < K) ? p.b(g, k0 + kk, col0 + c) : 0.0f;
+            rb[q] = (col0 + c < C && k0 + kk < K) ? p.b(g, k0 + kk, col0 + c) : 0.0f;
+        }
+    };
+    float acc[4][4] = {};
+    fetch(0);
+    for (int64_t k0 = 0; k0 < K; k0 += TK) {
+        __syncthreads();                       // the previous step's reads of LDS are done
+#pragma unroll
+        for (int q = 0; q < A_PER; ++q) {
+            const int e = tid + q * GEMM_THREADS;
+            int kk, r;
+            if (Problem::A_K_FAST) { kk = e % TK; r = e / TK; } else { r = e % TM; kk = e / TM; }
+            As[kk][r] = ra[q];
+        }
+#pragma unroll
+        for (int q = 0; q < B_PER; ++q) {
+            const int e = tid + q * GEMM_THREADS;
+            int kk, c;
+            if (Problem::B_C_FAST) { c = e % TN; kk = e / TN; } else { kk = e % TK; c = e / TK; }
+            Bs[kk][c] = rb[q];
         }
         __syncthreads();
+        if (k0 + TK < K) fetch(k0 + TK);
 #pragma unroll
         for (int kk = 0; kk < TK; ++kk) {
             float a[4], b[4];
@@ -147,7 +184,6 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(a[r], b[c], acc[r][c]);
         }
-        __syncthreads();
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r)
