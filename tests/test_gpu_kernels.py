@@ -226,3 +226,44 @@ def test_error_paths():
     with pytest.raises(nm.NetmaxError):
         nm.netmax_set_policy(ctx, bad, 0.1)
     nm.netmax_destroy(ctx)
+
+
+def test_maximum_worker_count(ora):
+    """M = 4096 (the largest the library accepts): tables, draws, one full iteration, consensus distance."""
+    w = workload("cfg3", M=4096, D=100)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp)
+    thr, last, wt = nm.netmax_get_tables(gpu.ctx, w.M)
+    assert np.array_equal(thr, o.T) and np.array_equal(last, o.last)
+    for it in range(3):
+        gpu.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it))
+    Xg = gpu.get("x").cpu().numpy()
+    assert rel_err_rows(Xg, o.X) < 1e-5
+    assert gpu.consensus_dist() == pytest.approx(ora.consensus_dist(Xg, w.D), rel=1e-9)   # of the same state
+    gpu.close()
+    with pytest.raises(nm.NetmaxError):
+        nm.netmax_init(M=4097, D=8, ld=2048, model=nm.NETMAX_FLAT, lr=0.1, rho=0.1, seed=1, P=np.eye(4097))
+
+
+@pytest.mark.parametrize("over", [
+    dict(M=2, batch=1, n_per_worker=1, dims=(3, 2)),                           # one sample, one draw
+    dict(M=3, batch=4, n_per_worker=6, dims=(5, 1)),                           # a single class: zero gradient
+    dict(M=2, batch=1024, n_per_worker=50, dims=(9, 4, 3)),                    # the largest batch
+    dict(M=2, batch=6, n_per_worker=9, dims=(6, 5, 4, 6, 5, 4, 3, 2)),         # seven layers, the maximum
+])
+def test_degenerate_perceptron_shapes(ora, over):
+    w = workload("cfg1", **over)
+    inp = inputs_of(w)
+    inp["labels"] = np.minimum(inp["labels"], w.dims[-1] - 1).astype(np.int32)   # the cluster recipe has 10 classes
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp)
+    for it in range(3):
+        gpu.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it))
+        G = gpu.get("g").cpu().numpy()
+        if w.dims[-1] == 1:
+            assert np.all(G == 0) and np.all(o.G == 0)
+        else:
+            assert rel_err_rows(G, o.G) < 1e-5
+    assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < 1e-5
+    gpu.close()
