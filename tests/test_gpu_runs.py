@@ -330,3 +330,8 @@ def test_graph_replay_matches_the_individual_calls(name, over):
         eager.run(100, 1, use_graph=True)
     assert e.value.code == nm.NETMAX_ESTATE
     eager.close()
+
+
+def test_smoke_entry_point():
+    import __graft_entry__
+    __graft_entry__.smoke()
