@@ -170,6 +170,14 @@ int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev);
  * Results are identical to the individual calls. */
 int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *peers_dev, int32_t use_graph);
 
+/* Worker-side time bookkeeping of Algorithm 2 (UpdateTimeVector) against a simulated network.  For every worker i
+ * with peer m = peers_dev[i]: ema_dev[i][m] = beta ema_dev[i][m] + (1 - beta) t_dev[i][m] (not for m = i) and, if
+ * clock_dev is not NULL, clock_dev[i] += t_dev[i][m].  t_dev, ema_dev: device float [M][M]; clock_dev: device
+ * float [M]; all caller-owned.  ema_dev is what the monitor would collect (Algorithm 1) and hand to
+ * netmax_generate_policy. */
+int netmax_update_times(netmax_ctx *ctx, const int32_t *peers_dev, const float *t_dev, float beta, float *ema_dev,
+                        float *clock_dev);
+
 /* Consensus distance sum_i ||x_i - mean_i x_i||^2 over the first D columns of the current parameters: the
  * complete-graph form of the model-difference penalty of Eq. (1).  fp64 accumulation, fixed summation
  * order.  Waits for the stream; out_host: host double. */

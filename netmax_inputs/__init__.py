@@ -15,5 +15,6 @@ from .policy import (  # noqa: F401
     link_speeds,
     policy_for,
     iteration_times,
+    dynamic_times,
 )
 from .data import make_shards, init_params, f32_to_bf16_bits, bf16_bits_to_f32  # noqa: F401

@@ -25,7 +25,7 @@ def link_speeds(recipe: str, M: int, seed: int = BASE_SEED) -> np.ndarray:
         s = np.where(g[:, None] == g[None, :], 12.0, 1.0)
     elif recipe == "racks8_lognormal":
         n_racks = 8 if M >= 8 else M
-        r = i // max(M // n_racks, 1)
+        r = np.minimum(i // max(M // n_racks, 1), n_racks - 1)
         R = rng.lognormal(0.0, 1.0, size=(n_racks, n_racks))
         R = np.triu(R) + np.triu(R, 1).T
         R[np.diag_indices(n_racks)] *= 10.0
@@ -92,3 +92,22 @@ def iteration_times(recipe: str, M: int, seed: int = BASE_SEED, compute: float =
     t = np.maximum(n, compute)
     np.fill_diagonal(t, compute)
     return t
+
+
+def dynamic_times(recipe: str, M: int, n_segments: int, seed: int = BASE_SEED, compute: float = 0.05):
+    """Iteration-time matrices of a network that changes: in every segment one randomly chosen link of the
+    base network is slowed down by a factor between 2 and 100 (log-uniform), and the slow link moves from
+    segment to segment (Section V-A "Network": one link slowed by 2x to 100x, changed every few minutes).
+    Returns a list of n_segments float64 M x M matrices."""
+    rng = np.random.default_rng(seed + 7)
+    base = iteration_times(recipe, M, seed, compute)
+    out = []
+    for _ in range(n_segments):
+        i = int(rng.integers(0, M))
+        j = int((i + 1 + rng.integers(0, M - 1)) % M)
+        f = float(np.exp(rng.uniform(np.log(2.0), np.log(100.0))))
+        t = base.copy()
+        t[i, j] *= f
+        t[j, i] *= f
+        out.append(t)
+    return out

@@ -178,6 +178,13 @@ def mix(Xcur: np.ndarray, G: np.ndarray, V: np.ndarray, peer: np.ndarray, w: np.
     return Xn
 
 
+def update_times(peer: np.ndarray, t: np.ndarray, beta: float, ema: np.ndarray, clock: Optional[np.ndarray] = None):
+    """Algorithm 2's UpdateTimeVector on a simulated network; ema [M, M] and clock [M] (float32) change in place."""
+    M = peer.shape[0]
+    lib().ora_update_times(C.c_int(M), _p(_chk(peer, np.int32)), _p(_chk(t, np.float32)), C.c_double(beta),
+                           _p(_chk(ema, np.float32)), _p(None if clock is None else _chk(clock, np.float32)))
+
+
 def consensus_dist(X: np.ndarray, D: Optional[int] = None) -> float:
     M, ld = X.shape
     return float(lib().ora_consensus_dist(C.c_int(M), C.c_int64(ld if D is None else D), C.c_int64(ld),

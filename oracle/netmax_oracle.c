@@ -399,6 +399,22 @@ void ora_mix_convex(int M, int64_t ld, const float *Xcur, const float *G, float 
     }
 }
 
+/* ------------------------------------------------------------------ iteration-time bookkeeping
+ * Algorithm 2, UpdateTimeVector: after an iteration with peer m the worker records the iteration time t_im and
+ * smooths it, T_i[m] <- beta T_i[m] + (1 - beta) t_im (exponential moving average, T_i starts at 0); the
+ * monitor later collects the matrix [T_i[m]] (Algorithm 1).  Here the recorded time comes from a given matrix
+ * t (a simulated network); clock[i] accumulates the time worker i has spent (t_ii for a self selection).
+ * ema and clock are float and updated in place; clock may be NULL. */
+void ora_update_times(int M, const int32_t *peer, const float *t, double beta, float *ema, float *clock)
+{
+    for (int i = 0; i < M; ++i) {
+        const int32_t m = peer[i];
+        const size_t e = (size_t)i * M + m;
+        if (m != i) ema[e] = (float)(beta * (double)ema[e] + (1.0 - beta) * (double)t[e]);
+        if (clock) clock[i] = (float)((double)clock[i] + (double)t[e]);
+    }
+}
+
 /* ------------------------------------------------------------------ consensus distance
  * CD = sum_i || x_i - xbar ||^2, xbar = (1/M) sum_i x_i, over the first D columns: the
  * complete-graph form of the model-difference penalty of Eq. (1)

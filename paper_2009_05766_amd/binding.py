@@ -22,7 +22,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times",
     "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -75,6 +75,7 @@ def load():
         "netmax_local_step": (C.c_int, [vp, u64]),
         "netmax_mix": (C.c_int, [vp, u64, vp]),
         "netmax_run": (C.c_int, [vp, u64, i32, vp, i32]),
+        "netmax_update_times": (C.c_int, [vp, vp, vp, f32, vp, vp]),
         "netmax_consensus_dist": (C.c_int, [vp, C.POINTER(C.c_double)]),
         "netmax_params": (vp, [vp]),
         "netmax_losses": (vp, [vp]),
@@ -224,6 +225,12 @@ def netmax_mix(ctx, it: int, peers):
 def netmax_run(ctx, first_iter: int, n_iters: int, peers, use_graph: bool = False):
     import torch
     _check(load().netmax_run(ctx, first_iter, n_iters, _dp(peers, torch.int32), int(use_graph)), ctx)
+
+
+def netmax_update_times(ctx, peers, t, beta: float, ema, clock=None):
+    import torch
+    _check(load().netmax_update_times(ctx, _dp(peers, torch.int32), _dp(t, torch.float32), beta, _dp(ema, torch.float32),
+                                      None if clock is None else _dp(clock, torch.float32)), ctx)
 
 
 def netmax_consensus_dist(ctx) -> float:

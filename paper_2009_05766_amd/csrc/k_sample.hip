@@ -57,6 +57,27 @@ void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uin
     hipLaunchKernelGGL(sample_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, s, M, B, n_rows, seed, iter, idx);
 }
 
+// Algorithm 2, UpdateTimeVector, on a simulated network: worker i records the time t[i][m] of its iteration with
+// peer m, smooths it into ema[i][m] (exponential moving average) and adds it to its clock.  One thread per worker.
+__global__ void __launch_bounds__(256) update_times_kernel(int M, const int32_t *__restrict__ peer,
+                                                           const float *__restrict__ t, float beta,
+                                                           float *__restrict__ ema, float *__restrict__ clock)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    int m = peer[i];
+    if ((unsigned)m >= (unsigned)M) m = i;
+    const size_t e = (size_t)i * M + m;
+    const float tim = t[e];
+    if (m != i) ema[e] = fmaf(beta, ema[e], (1.0f - beta) * tim);
+    if (clock) clock[i] += tim;
+}
+
+void launch_update_times(hipStream_t s, int M, const int32_t *peer, const float *t, float beta, float *ema, float *clock)
+{
+    hipLaunchKernelGGL(update_times_kernel, dim3((M + 255) / 256), dim3(256), 0, s, M, peer, t, beta, ema, clock);
+}
+
 __global__ void set_iteration_kernel(uint64_t *cell, uint64_t value) { *cell = value; }
 __global__ void bump_iteration_kernel(uint64_t *cell) { *cell += 1; }
 

@@ -20,6 +20,9 @@ void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uin
 void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, const IterRef &iter,
                        float *G);
 
+// Iteration-time bookkeeping of Algorithm 2 (UpdateTimeVector) against a given time matrix.
+void launch_update_times(hipStream_t s, int M, const int32_t *peer, const float *t, float beta, float *ema, float *clock);
+
 // The device cell of the iteration number used by graph replays: set it, advance it by one.
 void launch_set_iteration(hipStream_t s, uint64_t *cell, uint64_t value);
 void launch_bump_iteration(hipStream_t s, uint64_t *cell);

@@ -602,6 +602,16 @@ extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters,
     return NETMAX_OK;
 }
 
+extern "C" int netmax_update_times(netmax_ctx *ctx, const int32_t *peers_dev, const float *t_dev, float beta,
+                                   float *ema_dev, float *clock_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!peers_dev || !t_dev || !ema_dev || !(beta >= 0.0f) || !(beta <= 1.0f))
+        return fail(ctx, NETMAX_EINVAL, "NULL pointer or beta outside [0, 1]");
+    launch_update_times(ctx->stream, ctx->cfg.M, peers_dev, t_dev, beta, ema_dev, clock_dev);
+    return check_launch(ctx, "update_times");
+}
+
 extern "C" int netmax_consensus_dist(netmax_ctx *ctx, double *out_host)
 {
     if (!ctx) return NETMAX_EINVAL;

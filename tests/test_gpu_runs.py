@@ -249,23 +249,108 @@ def test_checkpoint_resume_is_bit_exact():
 
 def test_generated_policy_installed_mid_run():
     """The monitor's product (Algorithm 3) arriving during training (Algorithm 2, "received new policy"):
-    policy and rho generated from an iteration-time matrix by the library, installed after 10 iterations."""
+    policy and rho generated from an iteration-time matrix, installed after 10 iterations.  The library's policy
+    is checked against the oracle's; both runs then install the oracle's."""
     import paper_2009_05766_amd as nm
+    from oracle import policy as opol
     from netmax_inputs import iteration_times
     w = workload("cfg4", M=16, D=30000, T=30)
     inp = inputs_of(w)
     gpu, o = make_gpu(w, inp), make_oracle(w, inp)
     t = iteration_times("four_group_12", w.M)
-    pol = nm.netmax_generate_policy(t, float(np.float32(w.lr)), 40, 6)
-    rho = float(np.float32(pol["rho"]))
+    alpha = float(np.float32(w.lr))
+    ref = opol.generate_policy(t, alpha, 40, 6)
+    pol = nm.netmax_generate_policy(t, alpha, 40, 6)
+    assert pol["rho"] == pytest.approx(ref["rho"], rel=1e-12) and np.abs(pol["P"] - ref["P"]).max() < 1e-8
+    rho = float(np.float32(ref["rho"]))
     for it in range(w.T):
         if it == 10:
-            nm.netmax_set_policy(gpu.ctx, pol["P"], rho)
-            o.set_policy(pol["P"], rho)
+            nm.netmax_set_policy(gpu.ctx, ref["P"], rho)
+            o.set_policy(ref["P"], rho)
         gpu.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it))
     assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
     gpu.close()
+
+
+def test_dynamic_network_replay_with_monitor():
+    """Algorithm 1 + Algorithm 2's time bookkeeping on a network whose slow link moves (Section V-A): workers
+    smooth the iteration times they see, every segment the monitor turns the collected matrix into a policy.
+    GPU side: netmax_update_times / netmax_generate_policy through the Monitor; oracle side: ora_update_times and the
+    oracle's Algorithm 3.  Moving averages, clocks and the generated policies are compared; both runs then install
+    the oracle's policy, so that the trajectories stay comparable draw by draw."""
+    import oracle
+    from oracle import policy as opol
+    from netmax_inputs import dynamic_times, iteration_times
+    from paper_2009_05766_amd.monitor import Monitor
+    w = workload("cfg3", M=12, D=20000, T=90)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp)
+    alpha, K, R, beta = float(np.float32(w.lr)), 40, 6, 0.7
+    prior = 1.3 * iteration_times("two_tier_10", w.M)            # a biased first estimate, so that every average moves
+    nets = dynamic_times("two_tier_10", w.M, 3)
+    mon = Monitor(gpu, alpha=alpha, K=K, R=R, beta=beta, initial_times=prior)
+    ema = prior.astype(np.float32)
+    clock = np.zeros(w.M, np.float32)
+    it = 0
+    for t in nets:
+        mon.set_network(t)
+        t32 = t.astype(np.float32)
+        for _ in range(30):
+            peers = gpu.sample_peers(it)
+            mon.observe()
+            gpu.local_step(it)
+            gpu.mix(it)
+            po = o.step(it)
+            oracle.update_times(po, t32, beta, ema, clock)
+            assert np.array_equal(peers.cpu().numpy(), po)
+            it += 1
+        got = mon.collect()
+        assert np.allclose(got, ema, rtol=1e-6, atol=0)
+        assert np.allclose(mon.clock.cpu().numpy(), clock, rtol=1e-6)
+        ref = opol.generate_policy(ema.astype(np.float64), alpha, K, R)
+        mine = mon.reschedule()                                  # from the device's own averages
+        assert (ref is None) == (mine is None)
+        if ref is not None:
+            assert mine["t_conv"] == pytest.approx(ref["t_conv"], rel=1e-4)
+            if mine["rho"] == pytest.approx(ref["rho"], rel=1e-9) and mine["tbar"] == pytest.approx(ref["tbar"], rel=1e-5):
+                assert np.abs(mine["P"] - ref["P"]).max() < 1e-5
+            rho = float(np.float32(ref["rho"]))
+            mon.install(ref["P"], rho)
+            o.set_policy(ref["P"], rho)
+    assert (ema != prior.astype(np.float32)).sum() > 8 * w.M    # the averages moved
+    assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
+    assert gpu.consensus_dist() == pytest.approx(o.consensus_dist(), rel=1e-3)
+    gpu.close()
+
+
+def test_replay_driver_runs_segments():
+    """The replay driver (sampling, time bookkeeping, local step, mix, periodic rescheduling) against the same
+    sequence of library calls made by hand."""
+    from netmax_inputs import dynamic_times, iteration_times
+    from paper_2009_05766_amd.monitor import Monitor, replay
+    w = workload("cfg1")
+    inp = inputs_of(w)
+    nets = dynamic_times("two_tier_10", w.M, 2)
+    prior = iteration_times("two_tier_10", w.M)
+    kw = dict(alpha=float(np.float32(w.lr)), K=20, R=6, beta=0.5, initial_times=prior)
+    a, b = make_gpu(w, inp), make_gpu(w, inp)
+    hist = replay(a, Monitor(a, **kw), nets, 20)
+    mon = Monitor(b, **kw)
+    it = 0
+    for t in nets:
+        mon.set_network(t)
+        for _ in range(20):
+            b.sample_peers(it)
+            mon.observe()
+            b.local_step(it)
+            b.mix(it)
+            it += 1
+        mon.reschedule()
+    assert torch.equal(a.get("x"), b.get("x"))
+    assert len(hist) == 2 and hist[-1]["iteration"] == 40 and hist[-1]["sim_time"] == float(mon.clock.max().item())
+    assert hist[-1]["sim_time"] > 0 and np.isfinite(hist[-1]["consensus_dist"])
+    a.close(), b.close()
 
 
 def test_fixed_weight_averaging_mode():

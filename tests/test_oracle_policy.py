@@ -154,3 +154,39 @@ def test_workload_policies_are_feasible(ora, name):
     P, rho = policy_for(w)
     wt = ora.mix_weights(P, None, float(np.float32(w.lr)), rho)
     assert 0 < wt.max() <= 0.25 * (1 + 1e-6)      # rho = p_min / (4 lr)
+
+
+# ---- iteration-time bookkeeping (Algorithm 2, UpdateTimeVector) -------------------------------------------
+
+def test_update_times_constant_time_closed_form(ora):
+    """A link visited n times at a constant time t from a zero start holds (1 - beta^n) t (geometric sum)."""
+    M, beta = 4, 0.8
+    t = np.full((M, M), 3.0, np.float32)
+    ema = np.zeros((M, M), np.float32)
+    clock = np.zeros(M, np.float32)
+    peer = np.array([1, 2, 3, 0], np.int32)
+    for n in range(1, 12):
+        ora.update_times(peer, t, beta, ema, clock)
+        for i in range(M):
+            assert abs(ema[i, peer[i]] - (1 - beta ** n) * 3.0) < 1e-5
+    assert np.allclose(clock, 11 * 3.0)
+    touched = np.zeros((M, M), bool)
+    touched[np.arange(M), peer] = True
+    assert np.all(ema[~touched] == 0.0)
+
+
+def test_update_times_self_selection_and_limits(ora):
+    M = 3
+    t = np.arange(1, 10, dtype=np.float32).reshape(M, M)
+    ema = np.full((M, M), 7.0, np.float32)
+    clock = np.zeros(M, np.float32)
+    peer = np.array([0, 2, 1], np.int32)             # worker 0 selects itself
+    ora.update_times(peer, t, 0.0, ema, clock)    # beta = 0: the latest time replaces the average
+    assert ema[0, 0] == 7.0 and ema[1, 2] == t[1, 2] and ema[2, 1] == t[2, 1]
+    assert np.array_equal(clock, np.array([t[0, 0], t[1, 2], t[2, 1]], np.float32))
+    before = ema.copy()
+    ora.update_times(peer, t, 1.0, ema, None)     # beta = 1: the average never moves
+    assert np.array_equal(ema, before)
+    ema2 = np.zeros((M, M), np.float32)
+    ora.update_times(np.array([1, 0, 0], np.int32), t, 0.25, ema2, None)
+    assert np.isclose(ema2[0, 1], 0.75 * t[0, 1]) and ema2[1, 0] == np.float32(0.75 * t[1, 0]) and ema2[0, 2] == 0
