@@ -279,7 +279,8 @@ class NetMax:
         self.M, self.D, self.ld, self.batch = M, D, ld, batch
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
-        self.stream = torch.cuda.current_stream(self.device).cuda_stream
+        self._own = torch.cuda.current_stream(self.device)     # the stream every library call of this run uses
+        self.stream = self._own.cuda_stream
         self.ctx = netmax_init(M=M, D=D, ld=ld, model=model, dims=dims, batch=batch, gemm_in=gemm_in, lr=lr,
                                momentum=momentum, weight_decay=weight_decay, rho=rho, grad_sigma=grad_sigma,
                                seed=seed, strict_o3=strict_o3, P=P, adj=adj, stream=self.stream, mix_mode=mix_mode,
@@ -306,6 +307,15 @@ class NetMax:
             netmax_bind_data(self.ctx, self.feats, self.labels, shard_off)
 
     # ---- state access --------------------------------------------------------------------------
+    def _join(self):
+        """Orders the caller's current stream with the run's stream (they differ when the run was created under
+        another `torch.cuda.stream`): work queued on either is finished before the other goes on."""
+        import torch
+        cur = torch.cuda.current_stream(self.device)
+        if cur.cuda_stream != self.stream:
+            cur.synchronize()
+            self._own.synchronize()
+
     def _buffer(self, name: str):
         if name == "x":
             return self.params()
@@ -318,21 +328,25 @@ class NetMax:
             rows = torch.from_numpy(np.ascontiguousarray(rows, dtype=np.float32)).to(self.device)
         rows = rows.contiguous()
         assert rows.shape[0] == self.M and rows.shape[1] >= self.D
+        self._join()
         netmax_pack(self.ctx, rows, rows.shape[1], self._buffer(name))
-        torch.cuda.current_stream(self.device).synchronize()   # `rows` may be a temporary
+        self._own.synchronize()                                # `rows` may be a temporary
 
     def get(self, name: str, cols: Optional[int] = None):
         """Row-major device tensor [M, cols] of x (current), v or g; cols defaults to ld (padding as zeros)."""
         import torch
         cols = self.ld if cols is None else cols
         out = torch.zeros((self.M, cols), dtype=torch.float32, device=self.device)
+        self._join()
         netmax_unpack(self.ctx, self._buffer(name), out, cols)
+        self._join()
         return out
 
     def get_window(self, name: str, col0: int, width: int):
         """Row-major [M, width] copy of columns col0 .. col0+width-1 (inside one tile) without a full unpack."""
         assert col0 // NETMAX_TILE == (col0 + width - 1) // NETMAX_TILE
         t, o = divmod(col0, NETMAX_TILE)
+        self._join()
         buf = self._buffer(name).view(self.ld // NETMAX_TILE, self.M, NETMAX_TILE)
         return buf[t, :, o:o + width].contiguous()
 
@@ -371,7 +385,8 @@ class NetMax:
             return None
         out = torch.empty(self.M, dtype=torch.float32, device=self.device)
         hip = C.CDLL("libamdhip64.so")
-        torch.cuda.current_stream(self.device).synchronize()
+        self._join()
+        self._own.synchronize()
         rc = hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(p), C.c_size_t(4 * self.M), C.c_int(3))
         if rc != 0:
             raise RuntimeError(f"hipMemcpy of the loss vector failed with {rc}")

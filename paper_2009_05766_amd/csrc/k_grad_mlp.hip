@@ -13,24 +13,32 @@ namespace netmax {
 constexpr int TM = 64, TN = 64, TK = 32, GEMM_THREADS = 256;
 constexpr int MAX_BATCH = 1024;
 
-// Input of layer l for worker g, batch row r, feature k: the gathered data row for l = 0, else the
-// previous layer's activation (fp32, or its stored bfloat16 copy when the operands are bf16).
+// Where the input of a layer comes from: the gathered data rows (fp32 or bfloat16 storage) for the first
+// layer, else the previous layer's activation (fp32, or its stored bfloat16 copy when the operands are bf16).
+enum : int { IN_GATHER_F32 = 0, IN_GATHER_BF16 = 1, IN_ACT_F32 = 2, IN_ACT_BF16 = 3 };
+
+__device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+// round != 0: the operand rounded to bfloat16; both candidates are computed, no branch
+__device__ __forceinline__ float maybe_round(float x, int round) { const float r = round_bf16(x); return round ? r : x; }
+
+// Input of layer l for worker g, batch row r, feature k.  bits<KIND>() is one unconditional load (the caller
+// passes coordinates inside the operand), value<KIND>() turns what was loaded into the multiplicand.
 struct LayerInput {
-    const void *feats; int feats_bf16; const int64_t *row0; const int32_t *idx; const float *act_prev;
+    const void *feats; const int64_t *row0; const int32_t *idx; const float *act_prev;
     const uint16_t *act_prev_bf16;
-    int B; int64_t din; int first; int round;
+    int B; int64_t din; int kind; int round;
     // rows: the worker's batch as absolute data rows (row0[g] + idx[g][b]), staged in LDS by the kernel
-    __device__ __forceinline__ float at(int g, int r, int64_t k, const int64_t *rows) const
+    template <int KIND> __device__ __forceinline__ uint32_t bits(int g, int r, int64_t k, const int64_t *rows) const
     {
-        if (first) {
-            const int64_t row = rows[r];
-            return feats_bf16 ? bf16_bits_to_float(((const uint16_t *)feats)[row * din + k])
-                              : (round ? round_bf16(((const float *)feats)[row * din + k])
-                                       : ((const float *)feats)[row * din + k]);
-        }
-        if (act_prev_bf16) return bf16_bits_to_float(act_prev_bf16[((size_t)g * B + r) * din + k]);
-        const float a = act_prev[((size_t)g * B + r) * din + k];
-        return round ? round_bf16(a) : a;
+        if constexpr (KIND == IN_GATHER_F32) return ((const uint32_t *)feats)[rows[r] * din + k];
+        else if constexpr (KIND == IN_GATHER_BF16) return ((const uint16_t *)feats)[rows[r] * din + k];
+        else if constexpr (KIND == IN_ACT_F32) return ((const uint32_t *)act_prev)[((size_t)g * B + r) * din + k];
+        else return act_prev_bf16[((size_t)g * B + r) * din + k];
+    }
+    template <int KIND> __device__ __forceinline__ float value(uint32_t u) const
+    {
+        if constexpr (KIND == IN_GATHER_BF16 || KIND == IN_ACT_BF16) return as_float(u << 16);
+        else return maybe_round(as_float(u), round);
     }
 };
 
@@ -42,14 +50,17 @@ struct FwdProblem {
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return din; }
-    __device__ bool gathers() const { return in.first != 0; }
     __device__ const LayerInput &input() const { return in; }
-    __device__ float a(int g, int64_t r, int64_t k, const int64_t *rows) const { return in.at(g, (int)r, k, rows); }
-    __device__ float b(int g, int64_t k, int64_t c) const
+    template <int AK> __device__ uint32_t a_bits(int g, int64_t r, int64_t k, const int64_t *rows) const
     {
-        const float w = X[tiled_offset(M, g, woff + k * dout + c)];
-        return round ? round_bf16(w) : w;
+        return in.bits<AK>(g, (int)r, k, rows);
     }
+    template <int AK> __device__ float a_val(uint32_t u) const { return in.value<AK>(u); }
+    __device__ uint32_t b_bits(int g, int64_t k, int64_t c) const
+    {
+        return ((const uint32_t *)X)[tiled_offset(M, g, woff + k * dout + c)];
+    }
+    __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
         float z = acc + X[tiled_offset(M, g, woff + din * dout + c)];
@@ -71,18 +82,17 @@ struct DgradProblem {
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return din; }
     __device__ int64_t depth() const { return dout; }
-    __device__ bool gathers() const { return false; }
     __device__ LayerInput input() const { return LayerInput{}; }
-    __device__ float a(int g, int64_t r, int64_t k, const int64_t *) const
+    template <int AK> __device__ uint32_t a_bits(int g, int64_t r, int64_t k, const int64_t *) const
     {
-        const float d = dz[((size_t)g * B + r) * dout + k];
-        return round ? round_bf16(d) : d;
+        return ((const uint32_t *)dz)[((size_t)g * B + r) * dout + k];
     }
-    __device__ float b(int g, int64_t k, int64_t c) const
+    template <int AK> __device__ float a_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    __device__ uint32_t b_bits(int g, int64_t k, int64_t c) const
     {
-        const float w = X[tiled_offset(M, g, woff + c * dout + k)];
-        return round ? round_bf16(w) : w;
+        return ((const uint32_t *)X)[tiled_offset(M, g, woff + c * dout + k)];
     }
+    __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
         const size_t q = ((size_t)g * B + r) * din + c;
@@ -104,14 +114,17 @@ struct WgradProblem {
     __device__ int64_t rows() const { return din; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return B; }
-    __device__ bool gathers() const { return in.first != 0; }
     __device__ const LayerInput &input() const { return in; }
-    __device__ float a(int g, int64_t r, int64_t k, const int64_t *rows) const { return in.at(g, (int)k, r, rows); }
-    __device__ float b(int g, int64_t k, int64_t c) const
+    template <int AK> __device__ uint32_t a_bits(int g, int64_t r, int64_t k, const int64_t *rows) const
     {
-        const float d = dz[((size_t)g * B + k) * dout + c];
-        return round ? round_bf16(d) : d;
+        return in.bits<AK>(g, (int)k, r, rows);
     }
+    template <int AK> __device__ float a_val(uint32_t u) const { return in.value<AK>(u); }
+    __device__ uint32_t b_bits(int g, int64_t k, int64_t c) const
+    {
+        return ((const uint32_t *)dz)[((size_t)g * B + k) * dout + c];
+    }
+    __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
         G[tiled_offset(M, g, woff + r * dout + c)] = acc;
@@ -119,9 +132,11 @@ struct WgradProblem {
 };
 
 // 64 x 64 output tile per workgroup, 4 x 4 per thread, K in steps of 32 through LDS.  The operands of the
-// next step are fetched into registers while the current step is multiplied; the worker's batch rows are
-// resolved once into LDS, so no load in the loop depends on another.
-template <class Problem>
+// next step are fetched into registers while the current step is multiplied.  Every fetch is a run of
+// unconditional loads: coordinates beyond the operand are clamped into it and the value is replaced by zero
+// afterwards, the operand's kind AK is a template parameter and the worker's batch rows are resolved once into
+// LDS, so that no load waits for a branch or for another load.
+template <class Problem, int AK>
 __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
 {
     __shared__ float As[TK][TM + 4];
@@ -131,27 +146,33 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
     const int64_t row0 = (int64_t)blockIdx.y * TM, col0 = (int64_t)blockIdx.x * TN;
     const int64_t R = p.rows(), C = p.cols(), K = p.depth();
     const int ty = tid / 16, tx = tid % 16;
-    if (p.gathers()) {
+    if (AK == IN_GATHER_F32 || AK == IN_GATHER_BF16) {
         const LayerInput in = p.input();
         for (int b = tid; b < in.B; b += GEMM_THREADS) s_rows[b] = in.row0[g] + in.idx[(size_t)g * in.B + b];
         __syncthreads();
     }
     constexpr int A_PER = (TM * TK) / GEMM_THREADS, B_PER = (TN * TK) / GEMM_THREADS;
-    float ra[A_PER], rb[B_PER];
+    uint32_t ra[A_PER], rb[B_PER];
+    unsigned a_ok = 0, b_ok = 0;          // bit q: element q of the fetch lies inside the operand
     auto fetch = [&](int64_t k0) {
+        a_ok = b_ok = 0;
 #pragma unroll
         for (int q = 0; q < A_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
             int kk, r;
             if (Problem::A_K_FAST) { kk = e % TK; r = e / TK; } else { r = e % TM; kk = e / TM; }
-            ra[q] = (row0 + r < R && k0 + kk < K) ? p.a(g, row0 + r, k0 + kk, s_rows) : 0.0f;
+            const int64_t rr = row0 + r, kq = k0 + kk;
+            a_ok |= (unsigned)(rr < R && kq < K) << q;
+            ra[q] = p.template a_bits<AK>(g, rr < R ? rr : R - 1, kq < K ? kq : K - 1, s_rows);
         }
 #pragma unroll
         for (int q = 0; q < B_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
             int kk, c;
             if (Problem::B_C_FAST) { c = e % TN; kk = e / TN; } else { kk = e % TK; c = e / TK; }
-            rb[q] = (col0 + c < C && k0 + kk < K) ? p.b(g, k0 + kk, col0 + c) : 0.0f;
+            const int64_t cc = col0 + c, kq = k0 + kk;
+            b_ok |= (unsigned)(cc < C && kq < K) << q;
+            rb[q] = p.b_bits(g, kq < K ? kq : K - 1, cc < C ? cc : C - 1);
         }
     };
     float acc[4][4] = {};
@@ -163,14 +184,16 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
             const int e = tid + q * GEMM_THREADS;
             int kk, r;
             if (Problem::A_K_FAST) { kk = e % TK; r = e / TK; } else { r = e % TM; kk = e / TM; }
-            As[kk][r] = ra[q];
+            const float v = p.template a_val<AK>(ra[q]);
+            As[kk][r] = ((a_ok >> q) & 1u) ? v : 0.0f;
         }
 #pragma unroll
         for (int q = 0; q < B_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
             int kk, c;
             if (Problem::B_C_FAST) { c = e % TN; kk = e / TN; } else { kk = e % TK; c = e / TK; }
-            Bs[kk][c] = rb[q];
+            const float v = p.b_val(rb[q]);
+            Bs[kk][c] = ((b_ok >> q) & 1u) ? v : 0.0f;
         }
         __syncthreads();
         if (k0 + TK < K) fetch(k0 + TK);
@@ -194,11 +217,27 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
         }
 }
 
-template <class Problem>
-static void launch_gemm(hipStream_t s, const Problem &p, int groups, int64_t rows, int64_t cols)
+template <class Problem> static dim3 gemm_grid(int groups, int64_t rows, int64_t cols)
 {
-    dim3 grid((unsigned)((cols + TN - 1) / TN), (unsigned)((rows + TM - 1) / TM), (unsigned)groups);
-    hipLaunchKernelGGL(grouped_gemm_kernel<Problem>, grid, dim3(GEMM_THREADS), 0, s, p);
+    return dim3((unsigned)((cols + TN - 1) / TN), (unsigned)((rows + TM - 1) / TM), (unsigned)groups);
+}
+
+static void launch_gemm(hipStream_t s, const DgradProblem &p, int groups, int64_t rows, int64_t cols)
+{
+    hipLaunchKernelGGL((grouped_gemm_kernel<DgradProblem, IN_ACT_F32>), gemm_grid<DgradProblem>(groups, rows, cols),
+                       dim3(GEMM_THREADS), 0, s, p);
+}
+
+template <class Problem>
+static void launch_gemm(hipStream_t s, const Problem &p, int kind, int groups, int64_t rows, int64_t cols)
+{
+    const dim3 grid = gemm_grid<Problem>(groups, rows, cols);
+    switch (kind) {
+    case IN_GATHER_F32: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_GATHER_F32>), grid, dim3(GEMM_THREADS), 0, s, p); break;
+    case IN_GATHER_BF16: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_GATHER_BF16>), grid, dim3(GEMM_THREADS), 0, s, p); break;
+    case IN_ACT_F32: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_ACT_F32>), grid, dim3(GEMM_THREADS), 0, s, p); break;
+    default: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_ACT_BF16>), grid, dim3(GEMM_THREADS), 0, s, p); break;
+    }
 }
 
 // Softmax cross-entropy on the logits: dz = (softmax - onehot) / B and the mean loss per worker.
@@ -272,10 +311,11 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
     const bool small_last = mfma_small_last_ok(p);
     auto input_of = [&](int l) {
         LayerInput in;
-        in.feats = p.feats; in.feats_bf16 = p.bf16; in.row0 = p.row0; in.idx = p.idx;
+        in.feats = p.feats; in.row0 = p.row0; in.idx = p.idx;
         in.act_prev = (l > 0 && !bf) ? p.act[l] : nullptr;
         in.act_prev_bf16 = (l > 0 && bf) ? p.hb[l] : nullptr;
-        in.B = p.B; in.din = p.dims[l]; in.first = (l == 0); in.round = p.bf16;
+        in.B = p.B; in.din = p.dims[l]; in.round = p.bf16;
+        in.kind = l == 0 ? (bf ? IN_GATHER_BF16 : IN_GATHER_F32) : (bf ? IN_ACT_BF16 : IN_ACT_F32);
         return in;
     };
     if (fast[0]) launch_gather_transpose(s, p);
@@ -296,7 +336,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
         f.out = (last || !bf) ? p.act[l + 1] : nullptr;
         f.out_bf16 = (bf && !last) ? p.hb[l + 1] : nullptr;
         f.out_bf16_t = (bf && !last) ? p.ht[l + 1] : nullptr;
-        launch_gemm(s, f, p.M, p.B, f.dout);
+        launch_gemm(s, f, f.in.kind, p.M, p.B, f.dout);
     }
     // loss and dZ of the last layer
     const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
@@ -314,7 +354,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
             WgradProblem wg;
             wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
             wg.B = p.B; wg.round = p.bf16; wg.G = G;
-            launch_gemm(s, wg, p.M, din, dout);
+            launch_gemm(s, wg, wg.in.kind, p.M, din, dout);
         }
         const int64_t nb = (int64_t)p.M * dout;
         hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, p.M, p.B, dout,
