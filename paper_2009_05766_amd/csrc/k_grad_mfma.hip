@@ -22,12 +22,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int MF_THREADS = 256;      // 4 waves
 constexpr int MF_BM = 128, MF_BN = 128;        // weight-gradient and forward tile
-constexpr int MF_BK = 32;                      // forward: contraction step
-constexpr int MF_PITCH = MF_BK + 8;            // 80 B rows: 16-byte aligned, conflict-free b128 reads
-// backward-data tile: 64 batch rows x 128 columns per workgroup, contraction in steps of 64;
-// waves 2 x 2, each 32 rows x 64 columns.  Two workgroups share a 128-row batch and the same weight block.
-constexpr int FD_BM = 64, FD_BN = 128, FD_BK = 64;
-constexpr int FD_PITCH = FD_BK + 8;  // LDS row pitch in bf16 elements (144 B: 16-byte aligned, conflict-free b128 reads)
+// Contraction step BK of the forward and backward-data kernels: operand rows in LDS are BK + 8 bf16 long
+// (16-byte aligned, conflict-free 128-bit reads).
 
 __device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 acc)
 {
@@ -54,39 +50,91 @@ static unsigned grouped_grid(int M, unsigned blocks_per_worker)
     return (unsigned)((M + MF_XCD - 1) / MF_XCD * MF_XCD) * blocks_per_worker;
 }
 
-// One contraction step of the 64 x 128 tile from LDS: As[m][k], Bs[n][k], both k-contiguous.
-__device__ __forceinline__ void tile_mma(const uint16_t (*As)[FD_PITCH], const uint16_t (*Bs)[FD_PITCH], int wm, int wn,
-                                         int lane, f32x16 (&acc)[2])
-{
-#pragma unroll
-    for (int ks = 0; ks < FD_BK / 16; ++ks) {
-        const int kofs = 16 * ks + 8 * (lane >> 5);
-        const u32x4 a = *reinterpret_cast<const u32x4 *>(&As[32 * wm + (lane & 31)][kofs]);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const u32x4 b = *reinterpret_cast<const u32x4 *>(&Bs[64 * wn + 32 * j + (lane & 31)][kofs]);
-            acc[j] = mfma_bf16(a, b, acc[j]);
-        }
-    }
-}
+// Position (in bf16 elements) of the 16-byte unit u of row n in an operand tile whose units are permuted
+// inside each row by the row's 16-block index.  The forward kernel writes its weight tile four rows apart per
+// lane (rows 4 nq + e); without the permutation those 8-byte writes meet only four bank groups (8-way
+// conflict), with it the conflict is 2-way; reads of whole units stay conflict-free.
+__device__ __forceinline__ int swz_unit(int n, int u) { return (u ^ ((n >> 4) & 3)) << 3; }
 
-// One contraction step of the 128 x 128 forward tile from LDS: As[m][k], Bs[n][k], both k-contiguous.
-__device__ __forceinline__ void tile_mma_128(const uint16_t (*As)[MF_PITCH], const uint16_t (*Bs)[MF_PITCH], int wm, int wn,
-                                         int lane, f32x16 (&acc)[2][2])
+// One contraction step of the 128 x 128 tile from LDS: As[m][k], Bs[n][k], both k-contiguous.
+// SWZ: Bs rows are stored with swz_unit().
+template <int BK, bool SWZ>
+__device__ __forceinline__ void tile_mma_128(const uint16_t (*As)[BK + 8], const uint16_t (*Bs)[BK + 8], int wm, int wn,
+                                             int lane, f32x16 (&acc)[2][2])
 {
 #pragma unroll
-    for (int ks = 0; ks < MF_BK / 16; ++ks) {
-        const int kofs = 16 * ks + 8 * (lane >> 5);
+    for (int ks = 0; ks < BK / 16; ++ks) {
+        const int u = 2 * ks + (lane >> 5);
         u32x4 a[2], b[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const u32x4 *>(&As[64 * wm + 32 * i + (lane & 31)][kofs]);
+        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const u32x4 *>(&As[64 * wm + 32 * i + (lane & 31)][8 * u]);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&Bs[64 * wn + 32 * j + (lane & 31)][kofs]);
+        for (int j = 0; j < 2; ++j) {
+            const int n = 64 * wn + 32 * j + (lane & 31);
+            b[j] = *reinterpret_cast<const u32x4 *>(&Bs[n][SWZ ? swz_unit(n, u) : 8 * u]);
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
     }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Leaving a 128 x 128 result tile (waves 2 x 2, 64 x 64 each, final fp32 values in acc) as bfloat16 in both
+// orientations.  The matrix-instruction layout gives a lane single elements of 32 different rows; written
+// straight to memory that is 2-byte and 8-byte stores.  The tile goes through LDS instead, once row-major and
+// once transposed, and leaves as whole 256-byte rows in 16-byte pieces.
+constexpr int ST_PITCH = 128 + 8;                      // bf16 elements per staged row (272 B)
+constexpr int ST_BYTES = 128 * ST_PITCH * 2;
+
+// T[row][col] = bf16(acc) for the whole tile (2-byte LDS writes; lanes 0..31 neighbouring columns)
+__device__ __forceinline__ void stage_rows(uint16_t (*T)[ST_PITCH], int wm, int wn, int lane, const f32x16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                T[64 * wm + 32 * i + d_row(lane, v)][64 * wn + 32 * j + (lane & 31)] = (uint16_t)bf16_bits(acc[i][j][v]);
+}
+// T[col][row] = bf16(acc): four consecutive rows per 8-byte LDS write
+__device__ __forceinline__ void stage_cols(uint16_t (*T)[ST_PITCH], int wm, int wn, int lane, const f32x16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                u32x2 packed;
+                packed.x = pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]);
+                packed.y = pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                *reinterpret_cast<u32x2 *>(&T[64 * wn + 32 * j + (lane & 31)][64 * wm + 32 * i + d_row(lane, 4 * q)]) = packed;
+            }
+}
+// 128 staged rows of `len` valid bf16 elements each -> dst + r * stride, 16 bytes per thread and piece;
+// only the first n_rows rows are written.
+__device__ __forceinline__ void flush_rows(const uint16_t (*T)[ST_PITCH], int t, int n_rows, int len, uint16_t *dst, size_t stride)
+{
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int chunk = t + q * MF_THREADS, r = chunk >> 4, c = (chunk & 15) * 8;
+        if (r < n_rows && c < len) *reinterpret_cast<u32x4 *>(dst + (size_t)r * stride + c) = *reinterpret_cast<const u32x4 *>(&T[r][c]);
+    }
+}
+// out[(g B + row) ld + c0 + col] and out_t[(g ld + c0 + col) B + row] from acc; all threads of the workgroup.
+__device__ __forceinline__ void store_tile_bf16(uint16_t (*T)[ST_PITCH], int wm, int wn, int lane, int t, const f32x16 (&acc)[2][2],
+                                                int g, int B, int64_t ld, int64_t c0, uint16_t *out, uint16_t *out_t)
+{
+    stage_rows(T, wm, wn, lane, acc);
+    __syncthreads();
+    flush_rows(T, t, B, 128, out + ((size_t)g * B) * ld + c0, (size_t)ld);
+    __syncthreads();
+    stage_cols(T, wm, wn, lane, acc);
+    __syncthreads();
+    flush_rows(T, t, 128, B, out_t + ((size_t)g * ld + c0) * B, (size_t)B);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -102,25 +150,32 @@ struct FwdMfmaArgs {
     uint16_t *out, *out_t;
 };
 
-template <bool FIRST>
-__global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) fwd_mfma_kernel(FwdMfmaArgs p)
+template <bool FIRST, int BK>
+__device__ __forceinline__ void fwd_mfma_body(const FwdMfmaArgs &p)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t As[MF_BM][MF_PITCH];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[MF_BN][MF_PITCH];
+    constexpr int PITCH = BK + 8;
+    constexpr int A_CH = MF_BM * BK / 8 / MF_THREADS;      // 16-byte chunks of A per thread and step
+    constexpr int CPR = BK / 8;                            // chunks per A row
+    constexpr int W_BL = BK / 32;                          // 4 (k) x 4 (n) blocks of W per thread and step
+    // operand tiles during the contraction, the staging tile of the result afterwards
+    constexpr int OPERAND_BYTES = (MF_BM + MF_BN) * PITCH * 2;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[OPERAND_BYTES > ST_BYTES ? OPERAND_BYTES : ST_BYTES];
+    uint16_t (*As)[PITCH] = reinterpret_cast<uint16_t (*)[PITCH]>(smem);
+    uint16_t (*Bs)[PITCH] = reinterpret_cast<uint16_t (*)[PITCH]>(smem + MF_BM * PITCH * 2);
+    uint16_t (*T)[ST_PITCH] = reinterpret_cast<uint16_t (*)[ST_PITCH]>(smem);
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     int g;
     unsigned nblk;
     if (!decode_group(blockIdx.x, (unsigned)(p.dout / MF_BN), p.M, g, nblk)) return;
     const int64_t n0 = (int64_t)nblk * MF_BN;
 
-    // A: two 16-byte chunks per thread: rows ar[c], k offset 8 * (chunk % 4)
-    const uint16_t *a_src[2];
-    int a_row[2], a_k[2];
+    const uint16_t *a_src[A_CH];
+    int a_row[A_CH], a_k[A_CH];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < A_CH; ++c) {
         const int chunk = t + c * MF_THREADS;
-        a_row[c] = chunk >> 2;
-        a_k[c] = (chunk & 3) * 8;
+        a_row[c] = chunk / CPR;
+        a_k[c] = (chunk % CPR) * 8;
         if (a_row[c] < p.B) {
             const int64_t row = FIRST ? p.row0[g] + p.idx[(size_t)g * p.B + a_row[c]] : (int64_t)g * p.B + a_row[c];
             a_src[c] = (FIRST ? p.feats : p.a_prev) + row * p.din + a_k[c];
@@ -128,9 +183,17 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
             a_src[c] = nullptr;
         }
     }
-    // W: a 4 (k) x 4 (n) block per thread
+    // W: 4 (k) x 4 (n) blocks per thread.  One contraction step moves every load by BK rows of W =
+    // BK * dout columns of the parameter row, a whole number of layout tiles (dout is a multiple of 128),
+    // so the pointers advance by a constant.
     const int kg = t >> 5, nq = t & 31;
-    const int64_t w_col = p.woff + n0 + 4 * nq;
+    const float *w_src[W_BL][4];
+#pragma unroll
+    for (int q = 0; q < W_BL; ++q)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            w_src[q][r] = p.X + tiled_offset(p.M, g, p.woff + n0 + 4 * nq + (int64_t)(4 * (kg + 8 * q) + r) * p.dout);
+    const size_t w_step = (size_t)BK * (size_t)p.dout * (size_t)p.M;
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -140,163 +203,226 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    u32x4 ra[2];
-    f32x4_t rw[4];
+    u32x4 ra[A_CH];
+    f32x4_t rw[W_BL][4];
     auto fetch = [&](int64_t k0) {
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int c = 0; c < A_CH; ++c)
             ra[c] = a_src[c] ? *reinterpret_cast<const u32x4 *>(a_src[c] + k0) : (u32x4){0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            rw[r] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, w_col + (k0 + 4 * kg + r) * p.dout));
+        for (int q = 0; q < W_BL; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                rw[q][r] = *reinterpret_cast<const f32x4_t *>(w_src[q][r]);
+                w_src[q][r] += w_step;
+            }
     };
     auto stash = [&]() {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4 *>(&As[a_row[c]][a_k[c]]) = ra[c];
+        for (int c = 0; c < A_CH; ++c) *reinterpret_cast<u32x4 *>(&As[a_row[c]][a_k[c]]) = ra[c];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {   // column n = 4 nq + e gets its four consecutive k
-            u32x2 packed;
-            packed.x = pack_bf16x2(rw[0][e], rw[1][e]);
-            packed.y = pack_bf16x2(rw[2][e], rw[3][e]);
-            *reinterpret_cast<u32x2 *>(&Bs[4 * nq + e][4 * kg]) = packed;
-        }
+        for (int q = 0; q < W_BL; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {   // column n = 4 nq + e gets its four consecutive k
+                u32x2 packed;
+                packed.x = pack_bf16x2(rw[q][0][e], rw[q][1][e]);
+                packed.y = pack_bf16x2(rw[q][2][e], rw[q][3][e]);
+                const int n = 4 * nq + e, k4 = kg + 8 * q;       // k4: index of the group of four k
+                *reinterpret_cast<u32x2 *>(&Bs[n][swz_unit(n, k4 >> 1) + 4 * (k4 & 1)]) = packed;
+            }
     };
 
     fetch(0);
-    for (int64_t k0 = 0; k0 < p.din; k0 += MF_BK) {
+    for (int64_t k0 = 0; k0 < p.din; k0 += BK) {
         __syncthreads();            // the previous step's reads of LDS are done
         stash();
         __syncthreads();
-        if (k0 + MF_BK < p.din) fetch(k0 + MF_BK);   // overlaps with the matrix instructions below
-        tile_mma_128(As, Bs, wm, wn, lane, acc);
+        if (k0 + BK < p.din) fetch(k0 + BK);   // overlaps with the matrix instructions below
+        tile_mma_128<BK, true>(As, Bs, wm, wn, lane, acc);
     }
 
-    // epilogue: bias, ReLU, bf16, both layouts
+    // epilogue: bias, ReLU, then bf16 in both layouts through LDS
     const float *bias = p.X;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int64_t col = n0 + 64 * wn + 32 * j + (lane & 31);
         const float bcol = bias[tiled_offset(p.M, g, p.woff + p.din * p.dout + col)];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {           // four groups of four consecutive rows
-                const int row = 64 * wm + 32 * i + d_row(lane, 4 * q);
-                float z[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    z[e] = acc[i][j][4 * q + e] + bcol;
-                    if (p.relu) z[e] = z[e] > 0.0f ? z[e] : 0.0f;
-                }
-                if (row + 3 < p.B) {
-                    u32x2 packed;
-                    packed.x = pack_bf16x2(z[0], z[1]);
-                    packed.y = pack_bf16x2(z[2], z[3]);
-                    *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.dout + col) * p.B + row) = packed;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) p.out[((size_t)g * p.B + row + e) * p.dout + col] = (uint16_t)bf16_bits(z[e]);
-                }
+            for (int v = 0; v < 16; ++v) {
+                const float z = acc[i][j][v] + bcol;
+                acc[i][j][v] = (p.relu && !(z > 0.0f)) ? 0.0f : z;
             }
-        }
+    }
+    __syncthreads();                 // the last step's reads of the operand tiles are done
+    store_tile_bf16(T, wm, wn, lane, t, acc, g, p.B, p.dout, n0, p.out, p.out_t);
+}
+
+template <bool FIRST>
+__global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) fwd_mfma_kernel(FwdMfmaArgs p)
+{
+    fwd_mfma_body<FIRST, 32>(p);
+}
+// ---------------------------------------------------------------------------------------------------
+// Shared tail of the backward-data kernels.  The workgroup holds dA for all batch rows (waves 2 x 2, each
+// 64 rows x 64 columns in acc[i][j]) of `c0 .. c0 + 127`: applies the ReLU mask of the layer's input, writes
+// the error as bf16 [B][din] and transposed [din][B] (fp32 [B][din] too if out_f32 is given) and, because all
+// rows of a column are here, the column sums = the bias gradient of the layer below, in a fixed order.
+struct DgradOut {
+    const uint16_t *act;          // bf16 activations of this layer's input [M][B][din] (ReLU mask)
+    float *out_f32; uint16_t *out, *out_t;
+    float *G; int64_t boff;       // bias gradient of the layer below: G[tile layout, boff + column]
+};
+
+__device__ __forceinline__ void dgrad_tail(const DgradOut &o, int M, int g, int B, int64_t din, int64_t c0, int wm, int wn,
+                                           int lane, int t, f32x16 (&acc)[2][2], uint16_t (*T)[ST_PITCH], float (*red)[2][64])
+{
+    const int wave = 2 * wm + wn;
+    // the activations under the tile (ReLU mask) come in as whole rows
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int chunk = t + q * MF_THREADS, r = chunk >> 4, c = (chunk & 15) * 8;
+        if (r < B) *reinterpret_cast<u32x4 *>(&T[r][c]) = *reinterpret_cast<const u32x4 *>(o.act + ((size_t)g * B + r) * din + c0 + c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int cl = 64 * wn + 32 * j + (lane & 31);
+        float csum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = 64 * wm + 32 * i + d_row(lane, v);
+                const float d = (row < B && bf16_positive(T[row][cl])) ? acc[i][j][v] : 0.0f;
+                acc[i][j][v] = d;
+                csum += d;
+            }
+        red[wave][j][lane] = csum;
+    }
+    if (o.out_f32) {                 // only when the layer below runs on the general fp32-input kernels
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = 64 * wm + 32 * i + d_row(lane, v);
+                    if (row < B) o.out_f32[((size_t)g * B + row) * din + c0 + 64 * wn + 32 * j + (lane & 31)] = acc[i][j][v];
+                }
+    }
+    __syncthreads();                 // every mask is read before the tile is overwritten
+    store_tile_bf16(T, wm, wn, lane, t, acc, g, B, din, c0, o.out, o.out_t);
+    if (t < 128) {                   // red[] was complete before the barriers above
+        const int cwn = t >> 6, cj = (t >> 5) & 1, cl = t & 31;
+        float sum = 0.0f;
+#pragma unroll
+        for (int cwm = 0; cwm < 2; ++cwm)
+#pragma unroll
+            for (int half = 0; half < 2; ++half) sum += red[2 * cwm + cwn][cj][cl + 32 * half];
+        o.G[tiled_offset(M, g, o.boff + c0 + t)] = sum;
     }
 }
 
-// ---------------------------------------------------------------------------------------------------
-// Backward through a layer: dA = (dZ W^T) * [A > 0] for one worker, 64 batch rows and 128 input features
+// Backward through a layer: dA = (dZ W^T) * [A > 0] for one worker, all batch rows and 128 input features
 // (the output columns).  dZ: bf16 [B][dout]; W rows are contiguous along the contraction index, so they go
-// to LDS untransposed (256-byte row pieces per step).
-// Output: fp32 [B][din] (for the bias gradient), bf16 [B][din] and bf16 transposed [din][B].
+// to LDS untransposed (128-byte row pieces per step).
 struct DgradMfmaArgs {
     const uint16_t *dz; const float *X; int64_t woff; int M, B; int64_t din, dout;
-    const uint16_t *act;          // bf16 activations of this layer's input [M][B][din] (ReLU mask)
-    float *out_f32; uint16_t *out, *out_t;
+    DgradOut o;
 };
 
-__global__ void __launch_bounds__(MF_THREADS) dgrad_mfma_kernel(DgradMfmaArgs p)
+template <int BK>
+__device__ __forceinline__ void dgrad_mfma_body(const DgradMfmaArgs &p)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t As[FD_BM][FD_PITCH];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[FD_BN][FD_PITCH];
+    constexpr int PITCH = BK + 8;
+    constexpr int A_CH = MF_BM * BK / 8 / MF_THREADS;      // 16-byte chunks of dZ per thread and step
+    constexpr int CPR = BK / 8;
+    constexpr int W_CH = MF_BN * BK / 4 / MF_THREADS;      // 16-byte chunks of W per thread and step
+    constexpr int WPR = BK / 4;
+    constexpr int OPERAND_BYTES = (MF_BM + MF_BN) * PITCH * 2;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[OPERAND_BYTES > ST_BYTES ? OPERAND_BYTES : ST_BYTES];
+    uint16_t (*As)[PITCH] = reinterpret_cast<uint16_t (*)[PITCH]>(smem);
+    uint16_t (*Bs)[PITCH] = reinterpret_cast<uint16_t (*)[PITCH]>(smem + MF_BM * PITCH * 2);
+    uint16_t (*T)[ST_PITCH] = reinterpret_cast<uint16_t (*)[ST_PITCH]>(smem);
+    __shared__ float red[4][2][64];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const unsigned mblocks = (unsigned)((p.B + FD_BM - 1) / FD_BM);
     int g;
-    unsigned local;
-    if (!decode_group(blockIdx.x, (unsigned)(p.din / FD_BN) * mblocks, p.M, g, local)) return;
-    const int64_t c0 = (int64_t)(local / mblocks) * FD_BN;     // first input feature (output column) of this block
-    const int m0 = (int)(local % mblocks) * FD_BM;
+    unsigned cblk;
+    if (!decode_group(blockIdx.x, (unsigned)(p.din / MF_BN), p.M, g, cblk)) return;
+    const int64_t c0 = (int64_t)cblk * MF_BN;     // first input feature (output column) of this block
 
-    const uint16_t *a_src[2];
-    int a_row[2], a_k[2];
+    const uint16_t *a_src[A_CH];
+    int a_row[A_CH], a_k[A_CH];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < A_CH; ++c) {
         const int chunk = t + c * MF_THREADS;
-        a_row[c] = chunk >> 3;
-        a_k[c] = (chunk & 7) * 8;
-        a_src[c] = m0 + a_row[c] < p.B ? p.dz + ((size_t)g * p.B + m0 + a_row[c]) * p.dout + a_k[c] : nullptr;
+        a_row[c] = chunk / CPR;
+        a_k[c] = (chunk % CPR) * 8;
+        a_src[c] = a_row[c] < p.B ? p.dz + ((size_t)g * p.B + a_row[c]) * p.dout + a_k[c] : nullptr;
     }
-    f32x16 acc[2];
+    // W: 16-byte chunks, feature row = chunk / WPR, k offset 4 * (chunk % WPR)
+    int w_row[W_CH], w_k[W_CH];
+    int64_t w_col[W_CH];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int r = 0; r < W_CH; ++r) {
+        const int chunk = t + r * MF_THREADS;
+        w_row[r] = chunk / WPR;
+        w_k[r] = 4 * (chunk % WPR);
+        w_col[r] = p.woff + (c0 + w_row[r]) * p.dout + w_k[r];
+    }
+    f32x16 acc[2][2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // W: eight 128-bit loads per thread, chunk = t + 256 r: feature row = chunk / 16, quad = chunk % 16
-    u32x4 ra[2];
-    f32x4_t rw[8];
+    u32x4 ra[A_CH];
+    f32x4_t rw[W_CH];
     auto fetch = [&](int64_t k0) {
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int c = 0; c < A_CH; ++c)
             ra[c] = a_src[c] ? *reinterpret_cast<const u32x4 *>(a_src[c] + k0) : (u32x4){0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int chunk = t + r * MF_THREADS;
-            const int64_t feat = c0 + (chunk >> 4);
-            rw[r] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, p.woff + feat * p.dout + k0 + 4 * (chunk & 15)));
-        }
+        for (int r = 0; r < W_CH; ++r) rw[r] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, w_col[r] + k0));
     };
     auto stash = [&]() {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) *reinterpret_cast<u32x4 *>(&As[a_row[c]][a_k[c]]) = ra[c];
+        for (int c = 0; c < A_CH; ++c) *reinterpret_cast<u32x4 *>(&As[a_row[c]][a_k[c]]) = ra[c];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int chunk = t + r * MF_THREADS;
+        for (int r = 0; r < W_CH; ++r) {
             u32x2 packed;
             packed.x = pack_bf16x2(rw[r][0], rw[r][1]);
             packed.y = pack_bf16x2(rw[r][2], rw[r][3]);
-            *reinterpret_cast<u32x2 *>(&Bs[chunk >> 4][4 * (chunk & 15)]) = packed;
+            *reinterpret_cast<u32x2 *>(&Bs[w_row[r]][w_k[r]]) = packed;
         }
     };
 
-    fetch(0);
-    for (int64_t k0 = 0; k0 < p.dout; k0 += FD_BK) {
+    // The contraction starts at a different offset in every workgroup and wraps around: at any moment the
+    // workgroups then read different parts of their weight rows, which spreads the requests over the memory
+    // channels (all rows of W start at multiples of 4 dout bytes, the same offset in every row would meet
+    // the same few channels).
+    const int n_steps = (int)(p.dout / BK);
+    const int shift = (int)((cblk * 5u + (unsigned)g * 3u) % (unsigned)n_steps);
+    auto k_of = [&](int s) { int q = s + shift; if (q >= n_steps) q -= n_steps; return (int64_t)q * BK; };
+    fetch(k_of(0));
+    for (int s = 0; s < n_steps; ++s) {
         __syncthreads();
         stash();
         __syncthreads();
-        if (k0 + FD_BK < p.dout) fetch(k0 + FD_BK);
-        tile_mma(As, Bs, wm, wn, lane, acc);
+        if (s + 1 < n_steps) fetch(k_of(s + 1));
+        tile_mma_128<BK, false>(As, Bs, wm, wn, lane, acc);
     }
+    __syncthreads();                 // the last step's reads of the operand tiles are done
+    dgrad_tail(p.o, p.M, g, p.B, p.din, c0, wm, wn, lane, t, acc, T, red);
+}
 
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t col = c0 + 64 * wn + 32 * j + (lane & 31);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = m0 + 32 * wm + d_row(lane, 4 * q);
-            if (row + 3 < p.B) {
-                float d[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const size_t at = ((size_t)g * p.B + row + e) * p.din + col;
-                    d[e] = bf16_positive(p.act[at]) ? acc[j][4 * q + e] : 0.0f;
-                    p.out_f32[at] = d[e];
-                    p.out[at] = (uint16_t)bf16_bits(d[e]);
-                }
-                u32x2 packed;
-                packed.x = pack_bf16x2(d[0], d[1]);
-                packed.y = pack_bf16x2(d[2], d[3]);
-                *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.din + col) * p.B + row) = packed;
-            }
-        }
-    }
+__global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) dgrad_mfma_kernel(DgradMfmaArgs p)
+{
+    dgrad_mfma_body<32>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -510,16 +636,18 @@ __global__ void __launch_bounds__(MF_THREADS) wgrad_small_mfma_kernel(WgradSmall
 // One workgroup = one worker x 128 input features x all batch rows; waves 2 x 2, 64 x 64 each.
 struct DgradSmallArgs {
     const uint16_t *dz; const float *X; int64_t woff; int M, B; int64_t din, dout;
-    const uint16_t *act; float *out_f32; uint16_t *out, *out_t;
+    DgradOut o;
 };
 
 __global__ void __launch_bounds__(MF_THREADS) dgrad_small_mfma_kernel(DgradSmallArgs p)
 {
+    __shared__ __attribute__((aligned(16))) uint16_t T[128][ST_PITCH];
+    __shared__ float red[4][2][64];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
     int g;
     unsigned cblk;
     if (!decode_group(blockIdx.x, (unsigned)(p.din / 128), p.M, g, cblk)) return;
-    const int64_t c0 = (int64_t)cblk * 128 + 64 * wn;
+    const int64_t c0 = (int64_t)cblk * 128;
     const int steps = p.dout <= 16 ? 1 : 2;
     f32x16 acc[2][2];
 #pragma unroll
@@ -542,7 +670,7 @@ __global__ void __launch_bounds__(MF_THREADS) dgrad_small_mfma_kernel(DgradSmall
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int64_t feat = c0 + 32 * j + (lane & 31);
+            const int64_t feat = c0 + 64 * wn + 32 * j + (lane & 31);
             float w[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -554,38 +682,14 @@ __global__ void __launch_bounds__(MF_THREADS) dgrad_small_mfma_kernel(DgradSmall
 #pragma unroll
             for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
     }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t col = c0 + 32 * j + (lane & 31);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int row = 64 * wm + 32 * i + d_row(lane, 4 * q);
-                if (row + 3 < p.B) {
-                    float d[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const size_t at = ((size_t)g * p.B + row + e) * p.din + col;
-                        d[e] = bf16_positive(p.act[at]) ? acc[i][j][4 * q + e] : 0.0f;
-                        p.out_f32[at] = d[e];
-                        p.out[at] = (uint16_t)bf16_bits(d[e]);
-                    }
-                    u32x2 packed;
-                    packed.x = pack_bf16x2(d[0], d[1]);
-                    packed.y = pack_bf16x2(d[2], d[3]);
-                    *reinterpret_cast<u32x2 *>(p.out_t + ((size_t)g * p.din + col) * p.B + row) = packed;
-                }
-            }
-        }
-    }
+    dgrad_tail(p.o, p.M, g, p.B, p.din, c0, wm, wn, lane, t, acc, T, red);
 }
 
 // ---------------------------------------------------------------------------------------------------
 bool mfma_layer_ok(const MlpPlan &p, int l)
 {
     const int64_t din = p.dims[l], dout = p.dims[l + 1];
-    return p.bf16 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && dout % 128 == 0 && p.woff[l] % 4 == 0;   // din % 128 covers FD_BK
+    return p.bf16 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && dout % 128 == 0 && p.woff[l] % 4 == 0;
 }
 
 // the last layer when it has at most 32 outputs (see the "few classes" kernels above)
@@ -598,9 +702,19 @@ bool mfma_small_last_ok(const MlpPlan &p)
 
 void prepare_kernels()
 {
+
     // fwd_small_mfma_kernel keeps W^T in more than the default 64 KB of dynamic LDS
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_small_mfma_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, 32 * (SMALL_MAX_DIN + 8) * 2);
+}
+
+// Outputs of the backward-data kernel of layer l: the error of layer l - 1 and that layer's bias gradient.
+static DgradOut dgrad_out(const MlpPlan &p, int l, int cur, float *G, bool want_f32)
+{
+    DgradOut o;
+    o.act = p.hb[l]; o.out_f32 = want_f32 ? p.dz[cur ^ 1] : nullptr; o.out = p.dzb[cur ^ 1]; o.out_t = p.dzt[cur ^ 1];
+    o.G = G; o.boff = p.woff[l - 1] + p.dims[l - 1] * p.dims[l];
+    return o;
 }
 
 void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X)
@@ -622,12 +736,12 @@ void launch_wgrad_small(hipStream_t s, const MlpPlan &p, float *G, int cur)
     hipLaunchKernelGGL(wgrad_small_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / 128))), dim3(MF_THREADS), 0, s, a);
 }
 
-void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, int cur)
+void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, float *G, int cur, bool want_f32)
 {
     const int l = p.n_layers - 1;
     DgradSmallArgs a;
     a.dz = p.dzb[cur]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
-    a.act = p.hb[l]; a.out_f32 = p.dz[cur ^ 1]; a.out = p.dzb[cur ^ 1]; a.out_t = p.dzt[cur ^ 1];
+    a.o = dgrad_out(p, l, cur, G, want_f32);
     hipLaunchKernelGGL(dgrad_small_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / 128))), dim3(MF_THREADS), 0, s, a);
 }
 
@@ -648,14 +762,12 @@ void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X)
     else hipLaunchKernelGGL(fwd_mfma_kernel<false>, grid, dim3(MF_THREADS), 0, s, a);
 }
 
-void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, int cur)
+void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, float *G, int cur, bool want_f32)
 {
     DgradMfmaArgs a;
     a.dz = p.dzb[cur]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
-    a.act = p.hb[l]; a.out_f32 = p.dz[cur ^ 1]; a.out = p.dzb[cur ^ 1]; a.out_t = p.dzt[cur ^ 1];
-    hipLaunchKernelGGL(dgrad_mfma_kernel,
-                       dim3(grouped_grid(p.M, (unsigned)(a.din / FD_BN) * (unsigned)((p.B + FD_BM - 1) / FD_BM))),
-                       dim3(MF_THREADS), 0, s, a);
+    a.o = dgrad_out(p, l, cur, G, want_f32);
+    hipLaunchKernelGGL(dgrad_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / MF_BN))), dim3(MF_THREADS), 0, s, a);
 }
 
 void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur)

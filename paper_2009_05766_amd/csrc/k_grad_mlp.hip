@@ -241,11 +241,13 @@ static void launch_gemm(hipStream_t s, const Problem &p, int kind, int groups, i
 }
 
 // Softmax cross-entropy on the logits: dz = (softmax - onehot) / B and the mean loss per worker.
-// One workgroup per worker, one thread per batch row.
+// One workgroup per worker, one thread per batch row.  The workgroup then adds up the columns of dz (the
+// last layer's bias gradient, batch rows in order) and clears the padding behind the worker's gradient.
 __global__ void __launch_bounds__(1024)
 softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const int32_t *__restrict__ labels,
                     const int64_t *__restrict__ row0, const int32_t *__restrict__ idx, float *__restrict__ dz,
-                    uint16_t *__restrict__ dz_bf16, uint16_t *__restrict__ dz_bf16_t, float *__restrict__ loss)
+                    uint16_t *__restrict__ dz_bf16, uint16_t *__restrict__ dz_bf16_t, float *__restrict__ loss,
+                    int M, int64_t boff, int64_t D, int64_t ld, float *__restrict__ G)
 {
     __shared__ float red[1024];
     const int g = blockIdx.x, b = threadIdx.x;
@@ -271,7 +273,13 @@ softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const in
         }
     }
     red[b] = l;
-    __syncthreads();
+    __syncthreads();                 // also: every row of dz is written
+    for (int64_t o = b; o < C; o += blockDim.x) {
+        float s = 0.0f;
+        for (int r = 0; r < B; ++r) s += dz[((size_t)g * B + r) * C + o];
+        G[tiled_offset(M, g, boff + o)] = s;
+    }
+    for (int64_t e = b; e < ld - D; e += blockDim.x) G[tiled_offset(M, g, D + e)] = 0.0f;
     for (int stride = 512; stride > 0; stride >>= 1) {
         if (b < stride && b + stride < (int)blockDim.x) red[b] += red[b + stride];
         __syncthreads();
@@ -291,15 +299,6 @@ bias_grad_kernel(int M, int B, int64_t dout, const float *__restrict__ dz, int64
     float s = 0.0f;
     for (int b = 0; b < B; ++b) s += dz[((size_t)g * B + b) * dout + c];
     G[tiled_offset(M, g, boff + c)] = s;
-}
-
-__global__ void __launch_bounds__(256) zero_padding_kernel(int M, int64_t D, int64_t ld, float *__restrict__ G)
-{
-    const int64_t pad = ld - D;
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)M * pad) return;
-    const int g = (int)(t / pad);
-    G[tiled_offset(M, g, D + (t - (int64_t)g * pad))] = 0.0f;
 }
 
 void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
@@ -340,8 +339,12 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
     }
     // loss and dZ of the last layer
     const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
+    const int64_t D = p.woff[L - 1] + p.dims[L - 1] * p.dims[L] + p.dims[L];
     hipLaunchKernelGGL(softmax_xent_kernel, dim3(p.M), dim3(sm_threads), 0, s, p.B, p.dims[L], p.act[L], p.labels,
-                       p.row0, p.idx, p.dz[0], bf ? p.dzb[0] : nullptr, bf ? p.dzt[0] : nullptr, p.loss);
+                       p.row0, p.idx, p.dz[0], bf ? p.dzb[0] : nullptr, bf ? p.dzt[0] : nullptr, p.loss, p.M,
+                       p.woff[L - 1] + p.dims[L - 1] * p.dims[L], D, p.ld, G);
+    bool bias_done[8] = {};
+    bias_done[L - 1] = true;         // by the kernel above
     // backward
     int cur = 0;
     for (int l = L - 1; l >= 0; --l) {
@@ -356,14 +359,18 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
             wg.B = p.B; wg.round = p.bf16; wg.G = G;
             launch_gemm(s, wg, wg.in.kind, p.M, din, dout);
         }
-        const int64_t nb = (int64_t)p.M * dout;
-        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, p.M, p.B, dout,
-                           p.dz[cur], p.woff[l] + din * dout, G);
+        if (!bias_done[l]) {
+            const int64_t nb = (int64_t)p.M * dout;
+            hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, p.M, p.B, dout,
+                               p.dz[cur], p.woff[l] + din * dout, G);
+        }
         if (l > 0) {
             if (fast[l]) {
-                launch_dgrad_mfma(s, p, l, X, cur);
+                launch_dgrad_mfma(s, p, l, X, G, cur, !fast[l - 1]);
+                bias_done[l - 1] = true;
             } else if (l == L - 1 && small_last) {
-                launch_dgrad_small(s, p, X, cur);
+                launch_dgrad_small(s, p, X, G, cur, !fast[l - 1]);
+                bias_done[l - 1] = true;
             } else {
                 DgradProblem dg;
                 dg.dz = p.dz[cur]; dg.X = X; dg.act = bf ? nullptr : p.act[l]; dg.act_bf16 = bf ? p.hb[l] : nullptr;
@@ -375,11 +382,6 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
             }
             cur ^= 1;
         }
-    }
-    int64_t D = p.woff[L - 1] + p.dims[L - 1] * p.dims[L] + p.dims[L];
-    if (p.ld > D) {
-        const int64_t n = (int64_t)p.M * (p.ld - D);
-        hipLaunchKernelGGL(zero_padding_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.M, D, p.ld, G);
     }
 }
 

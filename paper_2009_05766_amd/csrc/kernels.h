@@ -70,12 +70,13 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G);
 bool mfma_layer_ok(const MlpPlan &p, int l);
 void launch_gather_transpose(hipStream_t s, const MlpPlan &p);
 void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X);
-void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, int cur);
+// also writes the bias gradient of layer l - 1 into G; want_f32: keep the fp32 copy of the error as well
+void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, float *G, int cur, bool want_f32);
 void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur);
 // Last layer with at most 32 outputs.
 bool mfma_small_last_ok(const MlpPlan &p);
 void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X);
 void launch_wgrad_small(hipStream_t s, const MlpPlan &p, float *G, int cur);
-void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, int cur);
+void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, float *G, int cur, bool want_f32);
 
 }  // namespace netmax
