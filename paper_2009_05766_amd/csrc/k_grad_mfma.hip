@@ -30,6 +30,13 @@ __device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 acc)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
 }
 
+// tiled_offset() with one 32 x 32 -> 64 bit multiply-add: j + (((j >> 11) (M - 1) + i) << 11); needs j < 2^43
+__device__ __forceinline__ size_t tiled_offset_fast(int M, int i, int64_t j)
+{
+    const uint64_t t = (uint64_t)(uint32_t)(j >> TILE_SHIFT) * (uint32_t)(M - 1) + (uint32_t)i;
+    return (size_t)j + (size_t)(t << TILE_SHIFT);
+}
+
 __device__ __forceinline__ int d_row(int lane, int v) { return 4 * (lane >> 5) + (v & 3) + 8 * (v >> 2); }
 
 // Workgroup id -> (worker, block inside the worker's GEMM).  Workgroup ids are dealt round-robin to the 8
@@ -426,8 +433,8 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Weight gradient: dW = A^T dZ for one worker and a strip of 128 rows of W.  The contraction runs over
-// the batch (<= 128), so whole operand blocks fit in LDS: the strip's A^T block [128][B] is loaded once,
+// Weight gradient: dW = A^T dZ for one worker and a strip of rows of W.  The contraction runs over
+// the batch (<= 128), so whole operand blocks fit in LDS: the strip's A^T block [rows][B] is loaded once,
 // then the workgroup walks along the strip in blocks of 128 columns; the dZ^T block of the next step is
 // fetched into registers while the matrix instructions of the current one run.  Both operands are the
 // transposed bf16 copies (batch-contiguous), read with coalesced 128-bit loads.  The fp32 product leaves
@@ -437,84 +444,97 @@ struct WgradMfmaArgs {
 };
 
 constexpr int WG_PITCH = 128 + 8;            // bf16 elements per operand row in LDS (272 B)
-constexpr int WG_CHUNKS = MF_BM * 128 / 8 / MF_THREADS;   // 16-byte chunks per thread and operand block at B = 128
 
-__global__ void __launch_bounds__(MF_THREADS) wgrad_mfma_kernel(WgradMfmaArgs p)
+// STRIP: rows of W per workgroup (128 or 64); waves 2 x 2, each STRIP / 2 rows x 64 columns of a 128-column block.
+template <int STRIP>
+__device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t At[MF_BM][WG_PITCH];
+    constexpr int RI = STRIP / 64;                               // 32-row tiles per wave
+    constexpr int A_CHUNKS = STRIP * 128 / 8 / MF_THREADS;       // 16-byte chunks per thread at B = 128
+    constexpr int Z_CHUNKS = MF_BN * 128 / 8 / MF_THREADS;
+    __shared__ __attribute__((aligned(16))) uint16_t At[STRIP][WG_PITCH];
     __shared__ __attribute__((aligned(16))) uint16_t Zt[MF_BN][WG_PITCH];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const unsigned nx = (unsigned)(p.dout / MF_BN), ny = (unsigned)(p.din / MF_BM);
+    const unsigned nx = (unsigned)(p.dout / MF_BN), ny = (unsigned)(p.din / STRIP);
     int g;
     unsigned strip;
     if (!decode_group(blockIdx.x, ny, p.M, g, strip)) return;
-    const int64_t r0 = (int64_t)strip * MF_BM;
+    const int64_t r0 = (int64_t)strip * STRIP;
     const int chunks_per_row = p.B >> 3;                        // 16-byte chunks; at most 16
-    const int n_chunks = MF_BM * chunks_per_row;
     const uint16_t *a_src = p.a_t + ((size_t)g * p.din + r0) * p.B;
     const uint16_t *z_src = p.dz_t + (size_t)g * p.dout * p.B;
 
-    int c_row[WG_CHUNKS], c_col[WG_CHUNKS];
 #pragma unroll
-    for (int q = 0; q < WG_CHUNKS; ++q) {
+    for (int q = 0; q < A_CHUNKS; ++q) {
+        const int c = t + q * MF_THREADS, row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
+        if (c < STRIP * chunks_per_row)
+            *reinterpret_cast<u32x4 *>(&At[row][col]) = *reinterpret_cast<const u32x4 *>(a_src + (size_t)row * p.B + col);
+    }
+    int c_row[Z_CHUNKS], c_col[Z_CHUNKS];
+#pragma unroll
+    for (int q = 0; q < Z_CHUNKS; ++q) {
         const int c = t + q * MF_THREADS;
         c_row[q] = c / chunks_per_row;
         c_col[q] = (c - c_row[q] * chunks_per_row) * 8;
     }
-    u32x4 rz[WG_CHUNKS];
+    const int n_chunks = MF_BN * chunks_per_row;
+    const int64_t lane_col = p.woff + (r0 + 32 * RI * wm + 4 * (lane >> 5)) * p.dout + 64 * wn + (lane & 31);
+    u32x4 rz[Z_CHUNKS];
     auto fetch_z = [&](unsigned nb) {
 #pragma unroll
-        for (int q = 0; q < WG_CHUNKS; ++q)
+        for (int q = 0; q < Z_CHUNKS; ++q)
             if (t + q * MF_THREADS < n_chunks)
                 rz[q] = *reinterpret_cast<const u32x4 *>(z_src + ((size_t)nb * MF_BN + c_row[q]) * p.B + c_col[q]);
     };
-#pragma unroll
-    for (int q = 0; q < WG_CHUNKS; ++q)
-        if (t + q * MF_THREADS < n_chunks)
-            *reinterpret_cast<u32x4 *>(&At[c_row[q]][c_col[q]]) =
-                *reinterpret_cast<const u32x4 *>(a_src + (size_t)c_row[q] * p.B + c_col[q]);
     fetch_z(0);
 
     for (unsigned nb = 0; nb < nx; ++nb) {
         __syncthreads();                                        // the previous block's reads of Zt are done
 #pragma unroll
-        for (int q = 0; q < WG_CHUNKS; ++q)
+        for (int q = 0; q < Z_CHUNKS; ++q)
             if (t + q * MF_THREADS < n_chunks) *reinterpret_cast<u32x4 *>(&Zt[c_row[q]][c_col[q]]) = rz[q];
         __syncthreads();
         if (nb + 1 < nx) fetch_z(nb + 1);
 
-        f32x16 acc[2][2];
+        f32x16 acc[RI][2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < RI; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
         for (int b0 = 0; b0 < p.B; b0 += 16) {
             const int kofs = b0 + 8 * (lane >> 5);
-            u32x4 a[2], b[2];
+            u32x4 a[RI], b[2];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const u32x4 *>(&At[64 * wm + 32 * i + (lane & 31)][kofs]);
+            for (int i = 0; i < RI; ++i) a[i] = *reinterpret_cast<const u32x4 *>(&At[32 * RI * wm + 32 * i + (lane & 31)][kofs]);
 #pragma unroll
             for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&Zt[64 * wn + 32 * j + (lane & 31)][kofs]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < RI; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
         }
-        const int64_t n0 = (int64_t)nb * MF_BN + 64 * wn;
+        // column index inside the parameter row = lane part (fixed) + a part that is the same for the whole wave
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < RI; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int64_t col = n0 + 32 * j + (lane & 31);
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int64_t row = r0 + 64 * wm + 32 * i + d_row(lane, v);
-                    __builtin_nontemporal_store(acc[i][j][v], p.G + tiled_offset(p.M, g, p.woff + row * p.dout + col));
+                    const int64_t uni = (int64_t)(32 * i + (v & 3) + 8 * (v >> 2)) * p.dout + (int64_t)nb * MF_BN + 32 * j;
+                    __builtin_nontemporal_store(acc[i][j][v], p.G + tiled_offset_fast(p.M, g, lane_col + uni));
                 }
-            }
     }
+}
+
+// 64-row strips: 51 KB of LDS, three workgroups per compute unit, whose arithmetic and store phases overlap
+// better than those of two workgroups with 128-row strips (measured: 13 % less time for both layers of the
+// 3072-1024-1024 perceptron).
+constexpr int WG_STRIP = 64;
+__global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3))) wgrad_mfma_kernel(WgradMfmaArgs p)
+{
+    wgrad_mfma_body<WG_STRIP>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -574,14 +594,22 @@ __global__ void __launch_bounds__(MF_THREADS) fwd_small_mfma_kernel(FwdSmallArgs
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t Wt[];      // [32][din + 8]
     const int g = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int pitch = (int)p.din + 8;
-    for (int e = t; e < 32 * pitch / 2; e += MF_THREADS) reinterpret_cast<uint32_t *>(Wt)[e] = 0u;
-    __syncthreads();
-    const int64_t n_w = p.din * p.dout;
-    for (int64_t e = t; e < n_w; e += MF_THREADS) {
-        const int64_t k = e / p.dout;
-        const int n = (int)(e - k * p.dout);
-        Wt[n * pitch + k] = (uint16_t)bf16_bits(p.X[tiled_offset(p.M, g, p.woff + e)]);
+    const int din = (int)p.din, dout = (int)p.dout, pitch = din + 8;
+    // rows dout .. 31 of Wt are the zero padding of the class dimension
+    for (int e = t + dout * pitch / 2; e < 32 * pitch / 2; e += MF_THREADS) reinterpret_cast<uint32_t *>(Wt)[e] = 0u;
+    // W[k][n] -> Wt[n][k]: the din x dout block is contiguous in the parameter row and starts at a multiple of four
+    // columns, so it is read as float4 (a float4 never straddles a layout tile)
+    {
+        const unsigned n_w = (unsigned)(din * dout), udout = (unsigned)dout;
+#pragma unroll 2
+        for (unsigned e4 = 4u * t; e4 < n_w; e4 += 4u * MF_THREADS) {
+            const f32x4_t w = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, p.woff + e4));
+#pragma unroll
+            for (unsigned c = 0; c < 4; ++c) {
+                const unsigned e = e4 + c, k = e / udout, n = e - k * udout;
+                Wt[n * pitch + k] = (uint16_t)bf16_bits(w[c]);
+            }
+        }
     }
     __syncthreads();
     for (int m0 = 32 * wave; m0 < p.B; m0 += 32 * (MF_THREADS / 64)) {
@@ -590,11 +618,17 @@ __global__ void __launch_bounds__(MF_THREADS) fwd_small_mfma_kernel(FwdSmallArgs
         f32x16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-        for (int64_t k0 = 0; k0 < p.din; k0 += 16)
-            acc = mfma_bf16(*reinterpret_cast<const u32x4 *>(a_ptr + k0), *reinterpret_cast<const u32x4 *>(b_ptr + k0), acc);
+        // din is a multiple of 128: eight steps of loads are issued before their matrix instructions
+        for (int k0 = 0; k0 < din; k0 += 128) {
+            u32x4 a[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) a[s] = *reinterpret_cast<const u32x4 *>(a_ptr + k0 + 16 * s);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) acc = mfma_bf16(a[s], *reinterpret_cast<const u32x4 *>(b_ptr + k0 + 16 * s), acc);
+        }
         const int col = lane & 31;
-        if (col < p.dout) {
-            const float bcol = p.X[tiled_offset(p.M, g, p.woff + n_w + col)];
+        if (col < dout) {
+            const float bcol = p.X[tiled_offset(p.M, g, p.woff + (int64_t)din * dout + col)];
 #pragma unroll
             for (int v = 0; v < 16; ++v) p.out[((size_t)g * p.B + m0 + d_row(lane, v)) * p.dout + col] = acc[v] + bcol;
         }
@@ -697,7 +731,8 @@ bool mfma_small_last_ok(const MlpPlan &p)
 {
     const int l = p.n_layers - 1;
     const int64_t din = p.dims[l], dout = p.dims[l + 1];
-    return p.bf16 && l > 0 && dout <= 32 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && din <= SMALL_MAX_DIN;
+    return p.bf16 && l > 0 && dout <= 32 && p.B % 32 == 0 && p.B <= 128 && din % 128 == 0 && din <= SMALL_MAX_DIN &&
+           p.woff[l] % 4 == 0;
 }
 
 void prepare_kernels()
@@ -775,7 +810,7 @@ void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur
     WgradMfmaArgs a;
     a.a_t = p.ht[l]; a.dz_t = p.dzt[cur]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.woff = p.woff[l]; a.G = G;
-    hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / MF_BM))), dim3(MF_THREADS), 0, s, a);
+    hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / WG_STRIP))), dim3(MF_THREADS), 0, s, a);
 }
 
 }  // namespace netmax

@@ -274,17 +274,37 @@ softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const in
     }
     red[b] = l;
     __syncthreads();                 // also: every row of dz is written
-    for (int64_t o = b; o < C; o += blockDim.x) {
-        float s = 0.0f;
-        for (int r = 0; r < B; ++r) s += dz[((size_t)g * B + r) * C + o];
-        G[tiled_offset(M, g, boff + o)] = s;
-    }
-    for (int64_t e = b; e < ld - D; e += blockDim.x) G[tiled_offset(M, g, D + e)] = 0.0f;
     for (int stride = 512; stride > 0; stride >>= 1) {
         if (b < stride && b + stride < (int)blockDim.x) red[b] += red[b + stride];
         __syncthreads();
     }
     if (b == 0) loss[g] = red[0] / (float)B;
+    for (int64_t e = b; e < ld - D; e += blockDim.x) G[tiled_offset(M, g, D + e)] = 0.0f;
+    // column sums of dz.  With few classes the rows are split over P groups of threads (rows part, part + P, ...),
+    // whose partial sums are then added in the order of the groups; otherwise one thread per column.
+    const int nt = (int)blockDim.x;
+    if (C <= nt / 2) {
+        const int c = (int)C, P = nt / c;
+        __syncthreads();             // red[0] has been read
+        if (b < c * P) {
+            const int o = b % c, part = b / c;
+            float s = 0.0f;
+            for (int r = part; r < B; r += P) s += dz[((size_t)g * B + r) * C + o];
+            red[b] = s;
+        }
+        __syncthreads();
+        if (b < c) {
+            float s = 0.0f;
+            for (int part = 0; part < P; ++part) s += red[part * c + b];
+            G[tiled_offset(M, g, boff + b)] = s;
+        }
+    } else {
+        for (int64_t o = b; o < C; o += nt) {
+            float s = 0.0f;
+            for (int r = 0; r < B; ++r) s += dz[((size_t)g * B + r) * C + o];
+            G[tiled_offset(M, g, boff + o)] = s;
+        }
+    }
 }
 
 // db = column sums of dZ; thread per (worker, output).
