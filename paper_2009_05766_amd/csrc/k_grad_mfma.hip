@@ -445,17 +445,19 @@ struct WgradMfmaArgs {
 
 constexpr int WG_PITCH = 128 + 8;            // bf16 elements per operand row in LDS (272 B)
 
-// STRIP: rows of W per workgroup (128 or 64); waves 2 x 2, each STRIP / 2 rows x 64 columns of a 128-column block.
-template <int STRIP>
+// STRIP: rows of W per workgroup (128 or 64), BN: columns per block step (128 or 64); waves 2 x 2, each
+// STRIP / 2 rows x BN / 2 columns.
+template <int STRIP, int BN>
 __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
 {
     constexpr int RI = STRIP / 64;                               // 32-row tiles per wave
     constexpr int A_CHUNKS = STRIP * 128 / 8 / MF_THREADS;       // 16-byte chunks per thread at B = 128
-    constexpr int Z_CHUNKS = MF_BN * 128 / 8 / MF_THREADS;
+    constexpr int CJ = BN / 64;                                  // 32-column tiles per wave
+    constexpr int Z_CHUNKS = BN * 128 / 8 / MF_THREADS;
     __shared__ __attribute__((aligned(16))) uint16_t At[STRIP][WG_PITCH];
-    __shared__ __attribute__((aligned(16))) uint16_t Zt[MF_BN][WG_PITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t Zt[BN][WG_PITCH];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const unsigned nx = (unsigned)(p.dout / MF_BN), ny = (unsigned)(p.din / STRIP);
+    const unsigned nx = (unsigned)(p.dout / BN), ny = (unsigned)(p.din / STRIP);
     int g;
     unsigned strip;
     if (!decode_group(blockIdx.x, ny, p.M, g, strip)) return;
@@ -477,14 +479,14 @@ __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
         c_row[q] = c / chunks_per_row;
         c_col[q] = (c - c_row[q] * chunks_per_row) * 8;
     }
-    const int n_chunks = MF_BN * chunks_per_row;
-    const int64_t lane_col = p.woff + (r0 + 32 * RI * wm + 4 * (lane >> 5)) * p.dout + 64 * wn + (lane & 31);
+    const int n_chunks = BN * chunks_per_row;
+    const int64_t lane_col = p.woff + (r0 + 32 * RI * wm + 4 * (lane >> 5)) * p.dout + 32 * CJ * wn + (lane & 31);
     u32x4 rz[Z_CHUNKS];
     auto fetch_z = [&](unsigned nb) {
 #pragma unroll
         for (int q = 0; q < Z_CHUNKS; ++q)
             if (t + q * MF_THREADS < n_chunks)
-                rz[q] = *reinterpret_cast<const u32x4 *>(z_src + ((size_t)nb * MF_BN + c_row[q]) * p.B + c_col[q]);
+                rz[q] = *reinterpret_cast<const u32x4 *>(z_src + ((size_t)nb * BN + c_row[q]) * p.B + c_col[q]);
     };
     fetch_z(0);
 
@@ -496,33 +498,33 @@ __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
         __syncthreads();
         if (nb + 1 < nx) fetch_z(nb + 1);
 
-        f32x16 acc[RI][2];
+        f32x16 acc[RI][CJ];
 #pragma unroll
         for (int i = 0; i < RI; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < CJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
         for (int b0 = 0; b0 < p.B; b0 += 16) {
             const int kofs = b0 + 8 * (lane >> 5);
-            u32x4 a[RI], b[2];
+            u32x4 a[RI], b[CJ];
 #pragma unroll
             for (int i = 0; i < RI; ++i) a[i] = *reinterpret_cast<const u32x4 *>(&At[32 * RI * wm + 32 * i + (lane & 31)][kofs]);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&Zt[64 * wn + 32 * j + (lane & 31)][kofs]);
+            for (int j = 0; j < CJ; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&Zt[32 * CJ * wn + 32 * j + (lane & 31)][kofs]);
 #pragma unroll
             for (int i = 0; i < RI; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < CJ; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
         }
         // column index inside the parameter row = lane part (fixed) + a part that is the same for the whole wave
 #pragma unroll
         for (int i = 0; i < RI; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < CJ; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int64_t uni = (int64_t)(32 * i + (v & 3) + 8 * (v >> 2)) * p.dout + (int64_t)nb * MF_BN + 32 * j;
+                    const int64_t uni = (int64_t)(32 * i + (v & 3) + 8 * (v >> 2)) * p.dout + (int64_t)nb * BN + 32 * j;
                     __builtin_nontemporal_store(acc[i][j][v], p.G + tiled_offset_fast(p.M, g, lane_col + uni));
                 }
     }
@@ -534,7 +536,7 @@ __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
 constexpr int WG_STRIP = 64;
 __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3))) wgrad_mfma_kernel(WgradMfmaArgs p)
 {
-    wgrad_mfma_body<WG_STRIP>(p);
+    wgrad_mfma_body<WG_STRIP, 128>(p);
 }
 
 // ---------------------------------------------------------------------------------------------------
