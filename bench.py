@@ -31,7 +31,7 @@ MIX_BYTES_MIN, MIX_BYTES_NAIVE = 20, 24
 _MIX_SOURCES = "23936c2060ea38f1.3f97687d5424e9a2.f872db49a5d92e6f"
 MEASURED_TRAFFIC = {"cfg3": {"sources": _MIX_SOURCES, "bytes": 14337682647},
                     "cfg4": {"sources": _MIX_SOURCES, "bytes": 12800500944},
-                    "cfg5": {"sources": _MIX_SOURCES, "bytes": 10777033072}}
+                    "cfg5": {"sources": _MIX_SOURCES, "bytes": 10777327661}}
 
 
 def mix_sources_digest() -> str:
