@@ -178,6 +178,36 @@ def mix(Xcur: np.ndarray, G: np.ndarray, V: np.ndarray, peer: np.ndarray, w: np.
     return Xn
 
 
+def activity(t: np.ndarray, P: np.ndarray, adj: Optional[np.ndarray] = None) -> np.ndarray:
+    """p_i of Eq. (d4) from the mean iteration times of Eq. (d3)."""
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    M = P.shape[0]
+    if adj is not None:
+        adj = np.ascontiguousarray(adj, dtype=np.uint8)
+    out = np.empty(M, dtype=np.float64)
+    lib().ora_activity(C.c_int(M), _p(t), _p(P), _p(adj), _p(out))
+    return out
+
+
+def async_draw(Tact: np.ndarray, last_act: int, T: np.ndarray, last: np.ndarray, seed: int, k: int):
+    """(i_k, m_k) of global step k of the asynchronous schedule."""
+    M = T.shape[0]
+    i, m = C.c_int32(0), C.c_int32(0)
+    lib().ora_async_draw(C.c_int(M), _p(_chk(Tact, np.uint32)), C.c_int32(last_act), _p(_chk(T, np.uint32)),
+                         _p(_chk(last, np.int32)), C.c_uint64(seed), C.c_uint64(k), C.byref(i), C.byref(m))
+    return int(i.value), int(m.value)
+
+
+def async_apply(X: np.ndarray, V: np.ndarray, g: np.ndarray, i: int, m: int, w: float, alpha: float, mu: float,
+                wd: float = 0.0):
+    """In-place update of the active worker's row of X and V."""
+    M, ld = X.shape
+    lib().ora_async_apply(C.c_int(M), C.c_int64(ld), _p(_chk(X, np.float32)), _p(_chk(V, np.float32)),
+                          _p(_chk(g, np.float32)), C.c_int(i), C.c_int(m), C.c_double(w), C.c_double(alpha),
+                          C.c_double(mu), C.c_double(wd))
+
+
 def update_times(peer: np.ndarray, t: np.ndarray, beta: float, ema: np.ndarray, clock: Optional[np.ndarray] = None):
     """Algorithm 2's UpdateTimeVector on a simulated network; ema [M, M] and clock [M] (float32) change in place."""
     M = peer.shape[0]
@@ -218,6 +248,20 @@ class Oracle:
 
     def sample_peers(self, it):
         return sample_peers(self.T, self.last, self.seed, it)
+
+    # ---- asynchronous schedule (one active worker per global step) ----
+    def set_activity(self, p_act):
+        """p_i of Eq. (d4); thresholds as for a policy row."""
+        p_act = np.ascontiguousarray(p_act, dtype=np.float64)
+        Tm, lastm = thresholds(np.tile(p_act, (self.M, 1)))
+        self.Tact, self.last_act = np.ascontiguousarray(Tm[0]), int(lastm[0])
+
+    def async_step(self, k):
+        """Global step k: draw (i_k, m_k), worker i_k's gradient at counter k, update of its row in place."""
+        i, m = async_draw(self.Tact, self.last_act, self.T, self.last, self.seed, k)
+        self.local_step(k)                       # all rows; only row i is used (same counters as the row alone)
+        async_apply(self.X, self.V, np.ascontiguousarray(self.G[i]), i, m, float(self.w[i, m]), self.lr, self.mu, self.wd)
+        return i, m
 
     def local_step(self, it):
         if len(self.dims) == 0:

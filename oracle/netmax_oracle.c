@@ -399,6 +399,57 @@ void ora_mix_convex(int M, int64_t ld, const float *Xcur, const float *G, float 
     }
 }
 
+/* ------------------------------------------------------------------ asynchronous schedule
+ * Section II-B and Eq. (c2)-(c4): the workers do not step together.  In global step k exactly one worker i_k is
+ * active.  A worker whose iterations take tbar_i = sum_m t_im p_im d_im on average (Eq. (d3)) is the active one
+ * with probability p_i = (1 / tbar_i) / sum_m (1 / tbar_m) (Eq. (d4)).  It pulls from m_k ~ P[i_k, :], takes
+ * its local step and mixes; every other copy stays: x^{k+1} = D^k (x^k - alpha g^k), g^k zero outside row i_k.
+ *
+ * Draws: i_k is found from word 0 of stream 3 at counter (0, 0, k) against the 32-bit cumulative thresholds of
+ * (p_i) (built like a policy row); m_k as in the synchronous schedule, stream 0 at counter (0, i_k, k). */
+void ora_activity(int M, const double *t, const double *P, const uint8_t *adj, double *p_act)
+{
+    double total = 0.0;
+    for (int i = 0; i < M; ++i) {
+        double tbar = 0.0;
+        for (int m = 0; m < M; ++m) {
+            const double d = (m == i) ? 0.0 : (adj ? (double)(adj[(size_t)i * M + m] != 0) : 1.0);
+            tbar += t[(size_t)i * M + m] * P[(size_t)i * M + m] * d;
+        }
+        p_act[i] = 1.0 / tbar;
+        total += p_act[i];
+    }
+    for (int i = 0; i < M; ++i) p_act[i] /= total;
+}
+
+void ora_async_draw(int M, const uint32_t *Tact, int32_t last_act, const uint32_t *T, const int32_t *last,
+                    uint64_t seed, uint64_t k, int32_t *i_out, int32_t *m_out)
+{
+    uint32_t r[4];
+    draw(seed, 3u, 0u, 0u, k, r);
+    const int32_t i = ora_peer_of_word(M, Tact, last_act, r[0]);
+    draw(seed, 0u, 0u, (uint32_t)i, k, r);
+    *i_out = i;
+    *m_out = ora_peer_of_word(M, T + (size_t)i * M, last[i], r[0]);
+}
+
+/* The active worker's update, in place: row i of X and V from its gradient g (one row) and row m of X. */
+void ora_async_apply(int M, int64_t ld, float *X, float *V, const float *g, int i, int m, double w, double alpha,
+                     double mu, double wd)
+{
+    (void)M;
+    float *x = X + (size_t)i * ld, *v = V + (size_t)i * ld;
+    const float *xp = X + (size_t)m * ld;
+    for (int64_t j = 0; j < ld; ++j) {
+        const double vn = mu * (double)v[j] + (double)g[j] + wd * (double)x[j];
+        const float vf = (float)vn;
+        const double h = (double)x[j] - alpha * (double)vf;
+        const double xpj = (m == i) ? 0.0 : (double)xp[j];          /* w = 0 for a self selection */
+        x[j] = (float)(h - w * (h - xpj));
+        v[j] = vf;
+    }
+}
+
 /* ------------------------------------------------------------------ iteration-time bookkeeping
  * Algorithm 2, UpdateTimeVector: after an iteration with peer m the worker records the iteration time t_im and
  * smooths it, T_i[m] <- beta T_i[m] + (1 - beta) t_im (exponential moving average, T_i starts at 0); the
