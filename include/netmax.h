@@ -170,6 +170,27 @@ int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev);
  * Results are identical to the individual calls. */
 int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *peers_dev, int32_t use_graph);
 
+/* ---- Asynchronous schedule (Section II-B, Eq. (c2)-(c4)) ----------------------------------------------------
+ * The workers do not step together: in global step k one worker i_k is active, pulls from m_k ~ P[i_k, :], takes
+ * its local step and mixes; every other copy stays as it is, x^{k+1} = D^k (x^k - alpha g^k).  A worker whose
+ * iterations take tbar_i = sum_m t_im p_im d_im on average (Eq. (d3)) is the active one with probability
+ * p_i = (1 / tbar_i) / sum_m (1 / tbar_m) (Eq. (d4)).
+ *
+ * netmax_activity: host helper, p_act_out[i] = p_i from iteration times t (host double [M][M], diagonal ignored),
+ * policy P (host double [M][M]) and adj (host, may be NULL).  NETMAX_EINVAL if a worker's mean time is not positive.
+ * netmax_set_activity: installs p_act (host double [M], non-negative, sum 1 within 1e-9) as 32-bit cumulative
+ * thresholds, as for a policy row.
+ * netmax_async_run: global steps first_step .. first_step + n_steps - 1 on the context's stream.  Step k draws i_k
+ * from word 0 of Philox stream 3 at counter (0, 0, k) and m_k from stream 0 at counter (0, i_k, k); the gradient
+ * of the active worker uses iteration number k in its counters.  active_dev / peers_dev: device int32 [n_steps],
+ * caller-owned, receive i_k and m_k.  x (the current buffer) and v are updated in place, no buffer flip; g
+ * receives the gradient (for perceptron models the gradient kernels compute all workers' rows and the active one is
+ * used).  Needs netmax_bind_state, netmax_set_activity and, for perceptron models, netmax_bind_data
+ * (else NETMAX_ESTATE).  Returns after enqueueing. */
+int netmax_activity(int32_t M, const double *t_host, const double *P_host, const uint8_t *adj, double *p_act_out);
+int netmax_set_activity(netmax_ctx *ctx, const double *p_act);
+int netmax_async_run(netmax_ctx *ctx, uint64_t first_step, uint64_t n_steps, int32_t *active_dev, int32_t *peers_dev);
+
 /* Worker-side time bookkeeping of Algorithm 2 (UpdateTimeVector) against a simulated network.  For every worker i
  * with peer m = peers_dev[i]: ema_dev[i][m] = beta ema_dev[i][m] + (1 - beta) t_dev[i][m] (not for m = i) and, if
  * clock_dev is not NULL, clock_dev[i] += t_dev[i][m].  t_dev, ema_dev: device float [M][M]; clock_dev: device

@@ -22,7 +22,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_activity", "netmax_set_activity", "netmax_async_run",
     "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -76,6 +76,9 @@ def load():
         "netmax_mix": (C.c_int, [vp, u64, vp]),
         "netmax_run": (C.c_int, [vp, u64, i32, vp, i32]),
         "netmax_update_times": (C.c_int, [vp, vp, vp, f32, vp, vp]),
+        "netmax_activity": (C.c_int, [C.c_int32, vp, vp, vp, vp]),
+        "netmax_set_activity": (C.c_int, [vp, vp]),
+        "netmax_async_run": (C.c_int, [vp, C.c_uint64, C.c_uint64, vp, vp]),
         "netmax_consensus_dist": (C.c_int, [vp, C.POINTER(C.c_double)]),
         "netmax_params": (vp, [vp]),
         "netmax_losses": (vp, [vp]),
@@ -225,6 +228,27 @@ def netmax_mix(ctx, it: int, peers):
 def netmax_run(ctx, first_iter: int, n_iters: int, peers, use_graph: bool = False):
     import torch
     _check(load().netmax_run(ctx, first_iter, n_iters, _dp(peers, torch.int32), int(use_graph)), ctx)
+
+
+def netmax_activity(t: np.ndarray, P: np.ndarray, adj: Optional[np.ndarray] = None) -> np.ndarray:
+    t, P, adj = _host(t, np.float64), _host(P, np.float64), _host(adj, np.uint8)
+    M = P.shape[0]
+    out = np.empty(M, np.float64)
+    rc = load().netmax_activity(M, _hp(t), _hp(P), _hp(adj), _hp(out))
+    if rc != NETMAX_OK:
+        raise NetmaxError(rc, "a worker's mean iteration time is not positive")
+    return out
+
+
+def netmax_set_activity(ctx, p_act: np.ndarray):
+    p_act = _host(p_act, np.float64)
+    _check(load().netmax_set_activity(ctx, _hp(p_act)), ctx)
+
+
+def netmax_async_run(ctx, first_step: int, n_steps: int, active, peers):
+    import torch
+    assert active.numel() >= n_steps and peers.numel() >= n_steps
+    _check(load().netmax_async_run(ctx, first_step, n_steps, _dp(active, torch.int32), _dp(peers, torch.int32)), ctx)
 
 
 def netmax_update_times(ctx, peers, t, beta: float, ema, clock=None):

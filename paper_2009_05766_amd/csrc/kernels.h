@@ -20,6 +20,13 @@ void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uin
 void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, const IterRef &iter,
                        float *G);
 
+// Asynchronous schedule: all (active worker, peer) draws of a run, and the in-place update of one worker's row.
+void launch_async_draw(hipStream_t s, int M, const uint32_t *act_thr, int act_last, const uint32_t *thr, const int32_t *last,
+                       uint64_t seed, uint64_t first, uint64_t n_steps, int32_t *active, int32_t *peers);
+void launch_async_row(hipStream_t s, bool synth, int M, int64_t D, int64_t ld, float *X, float *V, float *G,
+                      const int32_t *active, const int32_t *peers, const float *w, float alpha, float mu, float wd,
+                      float sigma, uint64_t seed, uint64_t k);
+
 // Iteration-time bookkeeping of Algorithm 2 (UpdateTimeVector) against a given time matrix.
 void launch_update_times(hipStream_t s, int M, const int32_t *peer, const float *t, float beta, float *ema, float *clock);
 

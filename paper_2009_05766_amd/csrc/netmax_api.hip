@@ -47,6 +47,9 @@ struct netmax_ctx {
     int64_t woff[NETMAX_MAX_LAYERS + 1] = {};
     // consensus distance
     double *d_partial = nullptr, *d_cd = nullptr;
+    // asynchronous schedule: thresholds of the activity probabilities p_i
+    uint32_t *d_act_thr = nullptr;
+    int act_last = -1;
     uint64_t iterations = 0;
     // graph replay (netmax_run): one captured iteration per direction of the parameter ping-pong
     float *x_first = nullptr;                 // the buffer bound as x_a: decides which graph an iteration uses
@@ -193,6 +196,7 @@ static void release(netmax_ctx *ctx)
     for (auto *p : ctx->d_dzb) (void)hipFree(p);
     for (auto *p : ctx->d_dzt) (void)hipFree(p);
     (void)hipFree(ctx->d_partial); (void)hipFree(ctx->d_cd);
+    (void)hipFree(ctx->d_act_thr);
     delete ctx;
 }
 
@@ -600,6 +604,87 @@ extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters,
         flip(ctx);
     }
     return NETMAX_OK;
+}
+
+// ---- asynchronous schedule ---------------------------------------------------------------------------
+
+extern "C" int netmax_activity(int32_t M, const double *t_host, const double *P_host, const uint8_t *adj, double *p_act_out)
+{
+    if (M < 1 || !t_host || !P_host || !p_act_out) return NETMAX_EINVAL;
+    double total = 0.0;
+    for (int i = 0; i < M; ++i) {
+        double tbar = 0.0;                                   // Eq. (d3); d_ii = 0
+        for (int m = 0; m < M; ++m)
+            if (m != i && (!adj || adj[(size_t)i * M + m])) tbar += t_host[(size_t)i * M + m] * P_host[(size_t)i * M + m];
+        if (!(tbar > 0.0) || !std::isfinite(tbar)) return NETMAX_EINVAL;
+        p_act_out[i] = 1.0 / tbar;
+        total += p_act_out[i];
+    }
+    for (int i = 0; i < M; ++i) p_act_out[i] /= total;       // Eq. (d4)
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_set_activity(netmax_ctx *ctx, const double *p_act)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!p_act) return fail(ctx, NETMAX_EINVAL, "p_act is NULL");
+    const int M = ctx->cfg.M;
+    double total = 0.0;
+    int tail = -1;
+    for (int i = 0; i < M; ++i) {
+        if (!(p_act[i] >= 0.0) || !std::isfinite(p_act[i])) return fail(ctx, NETMAX_EINVAL, "an activity probability is negative or not finite");
+        if (p_act[i] > 0.0) tail = i;
+        total += p_act[i];
+    }
+    if (tail < 0 || std::fabs(total - 1.0) > 1e-9) return fail(ctx, NETMAX_EINVAL, "the activity probabilities do not sum to 1");
+    std::vector<uint32_t> thr(M);
+    double running = 0.0;
+    for (int i = 0; i < M; ++i) {                            // the same fixed-point thresholds as a policy row
+        running += p_act[i];
+        uint64_t fixed;
+        if (i >= tail) {
+            fixed = 1ull << 32;
+        } else {
+            const double scaled = std::floor(std::ldexp(running, 32) + 0.5);
+            fixed = scaled >= 4294967296.0 ? (1ull << 32) : (uint64_t)scaled;
+        }
+        thr[i] = fixed > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)fixed;
+    }
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));         // a running step may still read the old thresholds
+    if (!ctx->d_act_thr) HIP_TRY(ctx, hipMalloc(&ctx->d_act_thr, (size_t)M * sizeof(uint32_t)));
+    HIP_TRY(ctx, hipMemcpy(ctx->d_act_thr, thr.data(), (size_t)M * sizeof(uint32_t), hipMemcpyHostToDevice));
+    ctx->act_last = tail;
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_async_run(netmax_ctx *ctx, uint64_t first_step, uint64_t n_steps, int32_t *active_dev, int32_t *peers_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!active_dev || !peers_dev) return fail(ctx, NETMAX_EINVAL, "active_dev or peers_dev is NULL");
+    if (n_steps > (1ull << 31)) return fail(ctx, NETMAX_EINVAL, "more than 2^31 steps in one call");
+    if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "netmax_bind_state has not been called");
+    if (ctx->act_last < 0) return fail(ctx, NETMAX_ESTATE, "netmax_set_activity has not been called");
+    const netmax_config &c = ctx->cfg;
+    if (c.model == NETMAX_MLP && !ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "netmax_bind_data has not been called");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    if (n_steps == 0) return NETMAX_OK;
+    launch_async_draw(ctx->stream, c.M, ctx->d_act_thr, ctx->act_last, ctx->d_thr, ctx->d_last, c.seed, first_step, n_steps,
+                      active_dev, peers_dev);
+    int rc = check_launch(ctx, "async_draw");
+    for (uint64_t s = 0; s < n_steps && rc == NETMAX_OK; ++s) {
+        const uint64_t k = first_step + s;
+        if (c.model == NETMAX_MLP) {
+            // the gradient kernels work on all workers at once; the active worker's row is the one that is used
+            rc = enqueue_local_step(ctx, IterRef{k, nullptr});
+            if (rc != NETMAX_OK) break;
+        }
+        launch_async_row(ctx->stream, c.model == NETMAX_FLAT, c.M, c.D, c.ld, ctx->x_cur, ctx->v, ctx->g, active_dev + s,
+                         peers_dev + s, ctx->d_w, c.lr, c.momentum, c.weight_decay, c.grad_sigma, c.seed, k);
+        rc = check_launch(ctx, "async_row");
+    }
+    if (rc == NETMAX_OK) ctx->iterations = first_step + n_steps;
+    return rc;
 }
 
 extern "C" int netmax_update_times(netmax_ctx *ctx, const int32_t *peers_dev, const float *t_dev, float beta,

@@ -34,7 +34,7 @@ struct IterRef {
 __device__ __forceinline__ uint64_t iteration_of(IterRef r) { return r.cell ? *r.cell : r.value; }
 
 // The library's draws: key = (seed_lo, seed_hi ^ stream), counter = (block, worker, iter_lo, iter_hi).
-enum : uint32_t { STREAM_PEER = 0u, STREAM_BATCH = 1u, STREAM_GRAD = 2u };
+enum : uint32_t { STREAM_PEER = 0u, STREAM_BATCH = 1u, STREAM_GRAD = 2u, STREAM_ACTIVE = 3u };
 
 __device__ __forceinline__ Words4 draw_block(uint64_t seed, uint32_t stream, uint32_t block, uint32_t worker,
                                              uint64_t iter)

@@ -420,3 +420,83 @@ def test_graph_replay_matches_the_individual_calls(name, over):
 def test_smoke_entry_point():
     import __graft_entry__
     __graft_entry__.smoke()
+
+
+def _async_pair(w, inp, **over):
+    import oracle
+    import paper_2009_05766_amd as nm
+    from netmax_inputs import iteration_times
+    gpu, o = make_gpu(w, inp, **over), make_oracle(w, inp, **over)
+    p_act = oracle.activity(iteration_times(w.links, w.M), inp["P"])
+    assert np.allclose(nm.netmax_activity(iteration_times(w.links, w.M), inp["P"]), p_act, rtol=1e-13)
+    nm.netmax_set_activity(gpu.ctx, p_act)
+    o.set_activity(p_act)
+    return gpu, o
+
+
+def test_async_schedule_flat():
+    """One active worker per global step (Eq. (c2)-(c4)): draws bit-exact, the active rows within the run tolerance,
+    everybody else untouched; then a synchronous iteration on top of the asynchronously reached state."""
+    import paper_2009_05766_amd as nm
+    w = workload("cfg3", M=8, D=5000, T=10)
+    inp = inputs_of(w)
+    gpu, o = _async_pair(w, inp)
+    n = 160
+    active = torch.zeros(n, dtype=torch.int32, device="cuda")
+    peers = torch.zeros(n, dtype=torch.int32, device="cuda")
+    nm.netmax_async_run(gpu.ctx, 0, 100, active, peers)
+    nm.netmax_async_run(gpu.ctx, 100, 60, active[100:], peers[100:])     # a run continues where the last one stopped
+    want = np.array([o.async_step(k) for k in range(n)], dtype=np.int32)
+    assert np.array_equal(active.cpu().numpy(), want[:, 0]) and np.array_equal(peers.cpu().numpy(), want[:, 1])
+    assert len(set(want[:, 0])) == w.M
+    assert nm.netmax_iteration(gpu.ctx) == n
+    assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
+    assert rel_err_rows(gpu.get("v").cpu().numpy(), o.V) < TOL_RUN
+    i_last = int(want[-1, 0])
+    assert np.allclose(gpu.get("g").cpu().numpy()[i_last], o.G[i_last], rtol=0, atol=2e-6 * w.grad_sigma * 6)
+    assert gpu.consensus_dist() == pytest.approx(o.consensus_dist(), rel=1e-3)
+    gpu.step(n)
+    assert np.array_equal(gpu.peers.cpu().numpy(), o.step(n))
+    assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
+    gpu.close()
+
+
+@pytest.mark.parametrize("name,over", [("cfg1", dict()), ("cfg5", dict(M=4, n_per_worker=128, dims=(256, 128, 128, 10), batch=64))])
+def test_async_schedule_perceptron(name, over):
+    import paper_2009_05766_amd as nm
+    w = workload(name, **over)
+    inp = inputs_of(w)
+    bf = w.gemm_in == "bf16"
+    gpu, o = _async_pair(w, inp)
+    if bf:
+        o.operands_bf16 = True
+    n = 24
+    active = torch.zeros(n, dtype=torch.int32, device="cuda")
+    peers = torch.zeros(n, dtype=torch.int32, device="cuda")
+    worst = 0.0
+    for k0 in range(0, n, 6):                       # windows: re-synchronised so that ReLU flips do not accumulate
+        o.X[:], o.V[:] = gpu.get("x").cpu().numpy(), gpu.get("v").cpu().numpy()
+        nm.netmax_async_run(gpu.ctx, k0, 6, active[k0:], peers[k0:])
+        want = np.array([o.async_step(k) for k in range(k0, k0 + 6)], dtype=np.int32)
+        assert np.array_equal(active[k0:k0 + 6].cpu().numpy(), want[:, 0])
+        assert np.array_equal(peers[k0:k0 + 6].cpu().numpy(), want[:, 1])
+        worst = max(worst, rel_err_rows(gpu.get("x").cpu().numpy(), o.X))
+    assert worst < (1e-3 if bf else TOL_RUN), worst
+    gpu.close()
+
+
+def test_async_schedule_needs_activities():
+    import paper_2009_05766_amd as nm
+    w = workload("cfg3", M=4, D=3000, T=5)
+    gpu = make_gpu(w, inputs_of(w))
+    a = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(nm.NetmaxError) as e:
+        nm.netmax_async_run(gpu.ctx, 0, 4, a, a.clone())
+    assert e.value.code == nm.NETMAX_ESTATE
+    with pytest.raises(nm.NetmaxError) as e:
+        nm.netmax_set_activity(gpu.ctx, np.array([0.5, 0.5, 0.5, -0.5]))
+    assert e.value.code == nm.NETMAX_EINVAL
+    nm.netmax_set_activity(gpu.ctx, np.array([0.0, 1.0, 0.0, 0.0]))
+    nm.netmax_async_run(gpu.ctx, 0, 4, a, a.clone())
+    assert a.cpu().numpy().tolist() == [1, 1, 1, 1]          # a worker of probability 0 is never active
+    gpu.close()

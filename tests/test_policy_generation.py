@@ -81,3 +81,25 @@ def test_argument_errors():
     with pytest.raises(nm.NetmaxError) as e:           # K = 1: rho = 0.5 / alpha leaves no room for (o3)
         nm.netmax_generate_policy(t, 0.1, 1, 4)
     assert e.value.code == nm.NETMAX_EINFEASIBLE
+
+
+def test_activity_matches_oracle():
+    """p_i of Eq. (d3)-(d4): the library's host helper against the oracle, with and without an adjacency mask."""
+    import oracle
+    rng = np.random.default_rng(5)
+    for M in (3, 8, 17):
+        t = rng.uniform(0.1, 5.0, (M, M))
+        P = rng.uniform(0.0, 1.0, (M, M))
+        np.fill_diagonal(P, 0.0)
+        adj = (rng.uniform(size=(M, M)) < 0.8).astype(np.uint8)
+        adj |= adj.T
+        adj[np.arange(M), (np.arange(M) + 1) % M] = 1        # every worker keeps a neighbour
+        adj[(np.arange(M) + 1) % M, np.arange(M)] = 1
+        np.fill_diagonal(adj, 0)
+        P1 = P / P.sum(1, keepdims=True)
+        assert np.allclose(nm.netmax_activity(t, P1), oracle.activity(t, P1), rtol=1e-13)
+        P2 = P * adj
+        P2 = P2 / P2.sum(1, keepdims=True)
+        assert np.allclose(nm.netmax_activity(t, P2, adj), oracle.activity(t, P2, adj), rtol=1e-13)
+    with pytest.raises(nm.NetmaxError):
+        nm.netmax_activity(np.zeros((3, 3)), np.full((3, 3), 1 / 3))
