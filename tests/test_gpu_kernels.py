@@ -169,6 +169,8 @@ GRAD_CASES = [
     ("cfg5", dict(M=5, batch=64, n_per_worker=100, dims=(256, 384, 128, 10))),   # matrix-core path, batch < 128
     ("cfg5", dict(M=3, batch=32, n_per_worker=40, dims=(128, 128, 256))),        # ... also for the last layer
     ("cfg5", dict(M=3, batch=96, n_per_worker=200, dims=(384, 128))),            # softmax regression, bf16
+    ("cfg5", dict(M=9, batch=96, n_per_worker=150, dims=(256, 256, 128, 10))),   # workers not a multiple of 8, batch 96
+    ("cfg5", dict(M=3, batch=64, n_per_worker=100, dims=(200, 128, 128, 10))),   # general first layer under matrix-core layers
 ]
 
 # Gradient tolerances, relative L2 per worker.  fp32 operands: fp32 accumulation over at most a few
