@@ -2,7 +2,7 @@
 // the stochastic gradient of Algorithm 2's first-step update, for all workers at once.  Every GEMM is
 // grouped, one group per worker, because each worker multiplies its own batch with its own weights.
 //
-// This file holds the general tiled kernels (any shape, fp32 FMA).  With bf16 operands the inputs of
+// This file holds the general tiled kernels (any shape, fp32 matrix instructions).  With bf16 operands the inputs of
 // every product are rounded to bfloat16 first and accumulated in fp32.
 #include "bf16.h"
 #include "kernels.h"
@@ -11,6 +11,7 @@
 namespace netmax {
 
 constexpr int TM = 64, TN = 64, TK = 32, GEMM_THREADS = 256;
+typedef float gemm_acc __attribute__((ext_vector_type(16)));
 constexpr int MAX_BATCH = 1024;
 
 // Where the input of a layer comes from: the gathered data rows (fp32 or bfloat16 storage) for the first
@@ -131,7 +132,10 @@ struct WgradProblem {
     }
 };
 
-// 64 x 64 output tile per workgroup, 4 x 4 per thread, K in steps of 32 through LDS.  The operands of the
+// 64 x 64 output tile per workgroup, one 32 x 32 quadrant per wave on v_mfma_f32_32x32x2_f32 (fp32 operands,
+// exact products, fp32 accumulation), K in steps of 32 through LDS.  Lane l of the instruction supplies
+// A[row l % 32][k = l / 32] and B[k = l / 32][col l % 32] and holds D[8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
+// in result register v.  The operands of the
 // next step are fetched into registers while the current step is multiplied.  Every fetch is a run of
 // unconditional loads: coordinates beyond the operand are clamped into it and the value is replaced by zero
 // afterwards, the operand's kind AK is a template parameter and the worker's batch rows are resolved once into
@@ -145,7 +149,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
     const int g = blockIdx.z, tid = threadIdx.x;
     const int64_t row0 = (int64_t)blockIdx.y * TM, col0 = (int64_t)blockIdx.x * TN;
     const int64_t R = p.rows(), C = p.cols(), K = p.depth();
-    const int ty = tid / 16, tx = tid % 16;
+    const int lane = tid & 63, wm = tid >> 7, wn = (tid >> 6) & 1;
     if (AK == IN_GATHER_F32 || AK == IN_GATHER_BF16) {
         const LayerInput in = p.input();
         for (int b = tid; b < in.B; b += GEMM_THREADS) s_rows[b] = in.row0[g] + in.idx[(size_t)g * in.B + b];
@@ -175,7 +179,9 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
             rb[q] = p.b_bits(g, kq < K ? kq : K - 1, cc < C ? cc : C - 1);
         }
     };
-    float acc[4][4] = {};
+    gemm_acc acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
     fetch(0);
     for (int64_t k0 = 0; k0 < K; k0 += TK) {
         __syncthreads();                       // the previous step's reads of LDS are done
@@ -198,23 +204,17 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
         __syncthreads();
         if (k0 + TK < K) fetch(k0 + TK);
 #pragma unroll
-        for (int kk = 0; kk < TK; ++kk) {
-            float a[4], b[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { a[e] = As[kk][ty * 4 + e]; b[e] = Bs[kk][tx * 4 + e]; }
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(a[r], b[c], acc[r][c]);
+        for (int kk = 0; kk < TK; kk += 2) {
+            const int k = kk + (lane >> 5);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[k][32 * wm + (lane & 31)], Bs[k][32 * wn + (lane & 31)], acc, 0, 0, 0);
         }
     }
+    const int64_t cc = col0 + 32 * wn + (lane & 31);
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int64_t rr = row0 + ty * 4 + r, cc = col0 + tx * 4 + c;
-            if (rr < R && cc < C) p.store(g, rr, cc, acc[r][c]);
-        }
+    for (int v = 0; v < 16; ++v) {
+        const int64_t rr = row0 + 32 * wm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (rr < R && cc < C) p.store(g, rr, cc, acc[v]);
+    }
 }
 
 template <class Problem> static dim3 gemm_grid(int groups, int64_t rows, int64_t cols)
