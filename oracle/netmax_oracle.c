@@ -16,9 +16,14 @@
  *   - Section V-A "Configurations": momentum SGD (momentum 0.9, weight decay) as
  *     the first-step optimiser;
  *   - Eq. (1): the pairwise model-difference penalty, whose complete-graph form
- *     is the consensus distance returned here.
- * All M workers step once per iteration and read the copies of the previous
- * iteration (the pulled x_m is the peer's copy from before its own update).
+ *     is the consensus distance returned here;
+ *   - Section II-B, Eq. (c2)-(c4), (d3), (d4): the asynchronous schedule with one
+ *     active worker per global step (ora_activity, ora_async_draw,
+ *     ora_async_apply);
+ *   - Algorithm 2, UpdateTimeVector: smoothed iteration times (ora_update_times).
+ * In the synchronous functions all M workers step once per iteration and read
+ * the copies of the previous iteration (the pulled x_m is the peer's copy from
+ * before its own update).
  *
  * Arithmetic: state is stored as float; every element of a result is computed
  * in double from the float inputs and rounded to float once.  Integer work
@@ -29,7 +34,10 @@
  * fixed point of identical copies; M=2 closed forms; expectation over the peer
  * draw == one step of Eq. (a4)/(a5); single active worker == D^k of Eq. (c4);
  * momentum apply == torch.optim.SGD; gradients == finite differences and
- * torch.autograd (fp64); consensus distance == brute-force pair sum.
+ * torch.autograd (fp64); consensus distance == brute-force pair sum; smoothed
+ * times == geometric closed form; asynchronous step == the active worker's row
+ * of the synchronous step == D^k (x - alpha g), draw frequencies, one-step
+ * second moment == x^T Y_P x of Eq. (d2).
  * Full trajectories of the five synthetic workloads have no published values:
  * parity unpinned in absolute terms for those (GPU vs oracle only).
  */
