@@ -58,6 +58,9 @@ def load():
     if not os.path.exists(LIB_PATH):
         from .build import build
         build()
+    # torch first: its ROCm build carries its own HIP runtime, and the library must bind to that copy (the one the
+    # device pointers and streams it is handed come from), not bring a second runtime into the process
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
     sig = {

@@ -500,3 +500,17 @@ def test_async_schedule_needs_activities():
     nm.netmax_async_run(gpu.ctx, 0, 4, a, a.clone())
     assert a.cpu().numpy().tolist() == [1, 1, 1, 1]          # a worker of probability 0 is never active
     gpu.close()
+
+
+def test_policy_comparison_demo_runs(capsys):
+    """The uniform-versus-generated-policy comparison at equal simulated time (a demonstration, not a claim):
+    it runs, both policies get the steps their mean iteration times allow, and both keep training."""
+    import json
+    from paper_2009_05766_amd import demo_policies
+    assert demo_policies.main(["--workload", "cfg1", "--time", "60", "--K", "20", "--R", "6"]) == 0
+    out = json.loads(capsys.readouterr().out)
+    runs = out["runs"]
+    assert set(runs) == {"uniform policy", "generated policy (Algorithm 3)"}
+    for r in runs.values():
+        assert r["steps"] == int(60 * r["steps_per_time"]) and r["steps"] > 20
+        assert np.isfinite(r["loss"]) and np.isfinite(r["consensus_dist"]) and r["loss"] < 2.4   # below ln 10 + margin
