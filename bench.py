@@ -96,6 +96,9 @@ def main() -> int:
     ap.add_argument("--mode", choices=("calls", "run", "graph"), default="calls",
                     help="calls: the three entry points per step, events around each phase (default); run: one "
                          "netmax_run call for all steps; graph: netmax_run replaying captured HIP graphs")
+    ap.add_argument("--fuse", action="store_true",
+                    help="with --mode run or graph, perceptron workloads on the matrix-core kernels: apply the update "
+                         "inside the weight-gradient kernels (netmax_set_fusion)")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="before the timed region, run this many plain device copies of the parameter matrix "
                          "(a kernel of known traffic, used to scale profiler byte counters)")
@@ -153,7 +156,12 @@ def main() -> int:
         e[3].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if args.fuse and args.mode == "calls":
+        print("bench.py: --fuse needs --mode run or --mode graph (the three separate entry points are never fused)", file=sys.stderr)
+        return 2
     if args.mode != "calls":
+        if args.fuse:
+            nm.netmax_set_fusion(gpu.ctx, True)
         first = args.warmup + K_ev
         gpu.run(first, 4, use_graph=args.mode == "graph")          # captures both directions outside the timed region
         torch.cuda.synchronize()
@@ -182,7 +190,7 @@ def main() -> int:
            "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_in == "bf16" else "f32",
            "data": "synthetic", "config": {"workload": describe(w), "M": w.M, "D": w.D, "iterations": K,
-                                           "launch": args.mode},
+                                           "launch": args.mode + ("+fused" if args.fuse else "")},
            "phase_ms": {"sample_peers": float(ms_sample), "local_step": float(ms_grad), "mix": float(ms_mix)},
            "consensus_distance": {"before": cd0, "after": cd1},
            "roofline": roofline}

@@ -170,6 +170,15 @@ int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev);
  * Results are identical to the individual calls. */
 int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *peers_dev, int32_t use_graph);
 
+/* netmax_run with the second-step update (Eq. (c0)/(c1)) applied by the weight-gradient kernels themselves: for the
+ * layers that run on the bf16 matrix-core kernels the product dW = A^T dZ is not written to g; the kernel that
+ * computes it reads x, v and the peer's x and writes x' and v' of those columns directly (Algorithm 2's two update
+ * steps on the gradient while it is still in registers).  A reduced mix covers all other columns.  x' and v' are
+ * the same as without fusion; g then holds only the columns the fused kernels do not cover.  on = 0 switches back.
+ * Affects netmax_run only (netmax_local_step and netmax_mix stay separate steps).  NETMAX_ESTATE for flat models
+ * and for models without such a layer.  Waits for the stream and drops captured graphs. */
+int netmax_set_fusion(netmax_ctx *ctx, int32_t on);
+
 /* ---- Asynchronous schedule (Section II-B, Eq. (c2)-(c4)) ----------------------------------------------------
  * The workers do not step together: in global step k one worker i_k is active, pulls from m_k ~ P[i_k, :], takes
  * its local step and mixes; every other copy stays as it is, x^{k+1} = D^k (x^k - alpha g^k).  A worker whose

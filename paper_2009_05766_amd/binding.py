@@ -22,7 +22,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_activity", "netmax_set_activity", "netmax_async_run",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_activity", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
     "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -79,6 +79,7 @@ def load():
         "netmax_mix": (C.c_int, [vp, u64, vp]),
         "netmax_run": (C.c_int, [vp, u64, i32, vp, i32]),
         "netmax_update_times": (C.c_int, [vp, vp, vp, f32, vp, vp]),
+        "netmax_set_fusion": (C.c_int, [vp, i32]),
         "netmax_activity": (C.c_int, [C.c_int32, vp, vp, vp, vp]),
         "netmax_set_activity": (C.c_int, [vp, vp]),
         "netmax_async_run": (C.c_int, [vp, C.c_uint64, C.c_uint64, vp, vp]),
@@ -231,6 +232,10 @@ def netmax_mix(ctx, it: int, peers):
 def netmax_run(ctx, first_iter: int, n_iters: int, peers, use_graph: bool = False):
     import torch
     _check(load().netmax_run(ctx, first_iter, n_iters, _dp(peers, torch.int32), int(use_graph)), ctx)
+
+
+def netmax_set_fusion(ctx, on: bool):
+    _check(load().netmax_set_fusion(ctx, int(bool(on))), ctx)
 
 
 def netmax_activity(t: np.ndarray, P: np.ndarray, adj: Optional[np.ndarray] = None) -> np.ndarray:

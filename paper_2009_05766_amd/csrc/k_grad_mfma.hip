@@ -540,6 +540,91 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Weight gradient with the second-step update applied in place of the store: one workgroup = one worker and one
+// 64-row x 128-column block of W.  The product dW = A^T dZ of the block is computed as above, turned through LDS
+// into rows, and every thread then updates four neighbouring parameters: v' = mu v + dW + wd x, h = x - alpha v',
+// x' = h - w (h - x_peer) (Eq. (c0), (c1)) with 128-bit loads and stores.  The gradient never goes to memory.
+// Workgroups are ordered block by block: all M workers of a block run side by side on one XCD (as the mix kernel
+// orders its tiles), so the block a worker pulls from its peer is in that XCD's L2.
+struct WgradMixArgs {
+    const uint16_t *a_t, *dz_t; int M, B; int64_t din, dout, woff;
+    MixArgs mix;
+};
+constexpr int WM_ROWS = 64, WM_COLS = 128;
+constexpr int WM_TILE_PITCH = WM_COLS + 4;           // floats per staged row
+
+__global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(3, 3))) wgrad_mix_mfma_kernel(WgradMixArgs p)
+{
+    constexpr int OPERAND_BYTES = (WM_ROWS + WM_COLS) * WG_PITCH * 2, TILE_BYTES = WM_ROWS * WM_TILE_PITCH * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[OPERAND_BYTES > TILE_BYTES ? OPERAND_BYTES : TILE_BYTES];
+    uint16_t (*At)[WG_PITCH] = reinterpret_cast<uint16_t (*)[WG_PITCH]>(smem);
+    uint16_t (*Zt)[WG_PITCH] = reinterpret_cast<uint16_t (*)[WG_PITCH]>(smem + WM_ROWS * WG_PITCH * 2);
+    float (*T)[WM_TILE_PITCH] = reinterpret_cast<float (*)[WM_TILE_PITCH]>(smem);
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    // workgroup id -> (block, worker): ids are dealt round-robin to the XCDs; a block's workers are consecutive slots
+    const unsigned nbx = (unsigned)(p.dout / WM_COLS), blocks = nbx * (unsigned)(p.din / WM_ROWS);
+    const unsigned xcd = blockIdx.x % MF_XCD, slot = blockIdx.x / MF_XCD;
+    const unsigned blk = (slot / (unsigned)p.M) * MF_XCD + xcd;
+    const int g = (int)(slot % (unsigned)p.M);
+    if (blk >= blocks) return;
+    const int64_t r0 = (int64_t)(blk / nbx) * WM_ROWS, n0 = (int64_t)(blk % nbx) * WM_COLS;
+    const int chunks_per_row = p.B >> 3;
+    const uint16_t *a_src = p.a_t + ((size_t)g * p.din + r0) * p.B;
+    const uint16_t *z_src = p.dz_t + ((size_t)g * p.dout + n0) * p.B;
+#pragma unroll
+    for (int q = 0; q < WM_ROWS * 16 / MF_THREADS; ++q) {
+        const int c = t + q * MF_THREADS, row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
+        if (c < WM_ROWS * chunks_per_row)
+            *reinterpret_cast<u32x4 *>(&At[row][col]) = *reinterpret_cast<const u32x4 *>(a_src + (size_t)row * p.B + col);
+    }
+#pragma unroll
+    for (int q = 0; q < WM_COLS * 16 / MF_THREADS; ++q) {
+        const int c = t + q * MF_THREADS, row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
+        if (c < WM_COLS * chunks_per_row)
+            *reinterpret_cast<u32x4 *>(&Zt[row][col]) = *reinterpret_cast<const u32x4 *>(z_src + (size_t)row * p.B + col);
+    }
+    __syncthreads();
+    f32x16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int b0 = 0; b0 < p.B; b0 += 16) {
+        const int kofs = b0 + 8 * (lane >> 5);
+        const u32x4 a = *reinterpret_cast<const u32x4 *>(&At[32 * wm + (lane & 31)][kofs]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            acc[j] = mfma_bf16(a, *reinterpret_cast<const u32x4 *>(&Zt[64 * wn + 32 * j + (lane & 31)][kofs]), acc[j]);
+    }
+    __syncthreads();                 // the operand tiles are read; their space becomes the staging tile
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) T[32 * wm + d_row(lane, v)][64 * wn + 32 * j + (lane & 31)] = acc[j][v];
+    __syncthreads();
+
+    const MixArgs &mx = p.mix;
+    int m = mx.peer[g];
+    if ((unsigned)m >= (unsigned)p.M) m = g;
+    const float wi = mx.w[(size_t)g * p.M + m];
+    const int cq = (t & 31) * 4, r_in = t >> 5;          // 32 lanes along the 128 columns, 8 rows per pass
+#pragma unroll 2
+    for (int pass = 0; pass < WM_ROWS / 8; ++pass) {
+        const int row = pass * 8 + r_in;
+        const int64_t j = p.woff + (r0 + row) * p.dout + n0 + cq;
+        const size_t own = tiled_offset_fast(p.M, g, j), other = tiled_offset_fast(p.M, m, j);
+        const f32x4_t x = *reinterpret_cast<const f32x4_t *>(mx.Xcur + own);
+        const f32x4_t xp = *reinterpret_cast<const f32x4_t *>(mx.Xcur + other);
+        const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(mx.V + own));
+        const f32x4_t gr = *reinterpret_cast<const f32x4_t *>(&T[row][cq]);
+        const f32x4_t vn = mx.mu * v + gr + mx.wd * x;
+        const f32x4_t h = x - mx.alpha * vn;
+        __builtin_nontemporal_store(h - wi * (h - xp), reinterpret_cast<f32x4_t *>(mx.Xnext + own));
+        __builtin_nontemporal_store(vn, reinterpret_cast<f32x4_t *>(mx.V + own));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
 // Transposed bf16 copy of each worker's gathered batch: out[g][k][b] = feats[row0[g] + idx[g][b]][k].
 // One workgroup = one worker x 64 features; the tile is turned in LDS.
 __global__ void __launch_bounds__(256)
@@ -805,6 +890,16 @@ void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, f
     a.dz = p.dzb[cur]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.o = dgrad_out(p, l, cur, G, want_f32);
     hipLaunchKernelGGL(dgrad_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / MF_BN))), dim3(MF_THREADS), 0, s, a);
+}
+
+void launch_wgrad_mix_mfma(hipStream_t s, const MlpPlan &p, int l, int cur, const MixArgs &mix)
+{
+    WgradMixArgs a;
+    a.a_t = p.ht[l]; a.dz_t = p.dzt[cur]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
+    a.woff = p.woff[l]; a.mix = mix;
+    const unsigned blocks = (unsigned)((a.din / WM_ROWS) * (a.dout / WM_COLS));
+    const unsigned grid = (blocks + MF_XCD - 1) / MF_XCD * MF_XCD * (unsigned)p.M;
+    hipLaunchKernelGGL(wgrad_mix_mfma_kernel, dim3(grid), dim3(MF_THREADS), 0, s, a);
 }
 
 void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur)

@@ -321,7 +321,7 @@ bias_grad_kernel(int M, int B, int64_t dout, const float *__restrict__ dz, int64
     G[tiled_offset(M, g, boff + c)] = s;
 }
 
-void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
+void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, const MixArgs *fuse)
 {
     const int L = p.n_layers;
     const bool bf = p.bf16 != 0;
@@ -370,7 +370,8 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G)
     for (int l = L - 1; l >= 0; --l) {
         const int64_t din = p.dims[l], dout = p.dims[l + 1];
         if (fast[l]) {
-            launch_wgrad_mfma(s, p, l, G, cur);
+            if (fuse) launch_wgrad_mix_mfma(s, p, l, cur, *fuse);
+            else launch_wgrad_mfma(s, p, l, G, cur);
         } else if (l == L - 1 && small_last) {
             launch_wgrad_small(s, p, G, cur);
         } else {

@@ -41,6 +41,14 @@ void prepare_kernels();
 void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float *G, float *V, float *Xnext,
                 const int32_t *peer, const float *w, float alpha, float mu, float wd);
 
+// The same update for a list of column tiles only, leaving out up to MIX_MAX_SKIP column ranges (multiples of four
+// columns) that another kernel has already updated.  tiles: device [n_tiles_listed].
+constexpr int MIX_MAX_SKIP = 8;
+struct MixSkip { int n; int64_t lo[MIX_MAX_SKIP], hi[MIX_MAX_SKIP]; };
+void launch_mix_subset(hipStream_t s, int M, const int32_t *tiles, int n_listed, const MixSkip &skip, const float *Xcur,
+                       const float *G, float *V, float *Xnext, const int32_t *peer, const float *w, float alpha, float mu,
+                       float wd);
+
 // Consensus distance: per-block partial sums (double), then a fixed-order final sum into out_dev[0].
 // partial must hold consensus_partials(ld) doubles.
 int consensus_partials(int64_t ld);
@@ -71,7 +79,14 @@ struct MlpPlan {
     uint16_t *dzb[2];       // [M][B][max width]
     uint16_t *dzt[2];       // [M][max width][B]
 };
-void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G);
+// What the second-step update needs besides the gradient: passed to the gradient code when the weight-gradient
+// kernels of the matrix-core layers apply the update themselves instead of writing the gradient.
+struct MixArgs {
+    const float *Xcur; float *V, *Xnext; const int32_t *peer; const float *w; float alpha, mu, wd;
+};
+// fuse != nullptr: layers accepted by mfma_layer_ok() do not write their weight gradient to G; they write
+// x' and v' of their weight columns (Eq. (c0)/(c1)) straight from the product.
+void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, const MixArgs *fuse = nullptr);
 
 // Matrix-core kernels (k_grad_mfma.hip) for layers that mfma_layer_ok() accepts.
 bool mfma_layer_ok(const MlpPlan &p, int l);
@@ -80,6 +95,7 @@ void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X);
 // also writes the bias gradient of layer l - 1 into G; want_f32: keep the fp32 copy of the error as well
 void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, float *G, int cur, bool want_f32);
 void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur);
+void launch_wgrad_mix_mfma(hipStream_t s, const MlpPlan &p, int l, int cur, const MixArgs &mix);
 // Last layer with at most 32 outputs.
 bool mfma_small_last_ok(const MlpPlan &p);
 void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X);

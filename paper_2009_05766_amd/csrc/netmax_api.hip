@@ -47,6 +47,11 @@ struct netmax_ctx {
     int64_t woff[NETMAX_MAX_LAYERS + 1] = {};
     // consensus distance
     double *d_partial = nullptr, *d_cd = nullptr;
+    // netmax_run with the update fused into the weight-gradient kernels: the tiles the separate mix still covers
+    bool fuse = false;
+    int32_t *d_fuse_tiles = nullptr;
+    int n_fuse_tiles = 0;
+    MixSkip fuse_skip{};
     // asynchronous schedule: thresholds of the activity probabilities p_i
     uint32_t *d_act_thr = nullptr;
     int act_last = -1;
@@ -196,7 +201,7 @@ static void release(netmax_ctx *ctx)
     for (auto *p : ctx->d_dzb) (void)hipFree(p);
     for (auto *p : ctx->d_dzt) (void)hipFree(p);
     (void)hipFree(ctx->d_partial); (void)hipFree(ctx->d_cd);
-    (void)hipFree(ctx->d_act_thr);
+    (void)hipFree(ctx->d_act_thr); (void)hipFree(ctx->d_fuse_tiles);
     delete ctx;
 }
 
@@ -468,14 +473,9 @@ static int enqueue_sample_peers(netmax_ctx *ctx, const IterRef &iter, int32_t *p
     return check_launch(ctx, "sample_peers");
 }
 
-static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter)
+static MlpPlan make_plan(const netmax_ctx *ctx)
 {
     const netmax_config &c = ctx->cfg;
-    if (c.model == NETMAX_FLAT) {
-        launch_synth_grad(ctx->stream, c.M, c.D, c.ld, c.grad_sigma, c.seed, iter, ctx->g);
-        return check_launch(ctx, "synth_grad");
-    }
-    launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
     MlpPlan p{};
     p.M = c.M; p.n_layers = c.n_layers; p.B = c.batch; p.ld = c.ld; p.bf16 = (c.gemm_in == NETMAX_BF16);
     for (int l = 0; l <= c.n_layers; ++l) {
@@ -485,15 +485,44 @@ static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter)
     for (int q = 0; q < 2; ++q) { p.dzb[q] = ctx->d_dzb[q]; p.dzt[q] = ctx->d_dzt[q]; }
     p.feats = ctx->feats; p.labels = ctx->labels; p.row0 = ctx->d_row0; p.idx = ctx->d_idx;
     p.dz[0] = ctx->d_dz[0]; p.dz[1] = ctx->d_dz[1]; p.loss = ctx->d_loss;
-    launch_mlp_grad(ctx->stream, p, ctx->x_cur, ctx->g);
+    return p;
+}
+
+static MixArgs mix_args(const netmax_ctx *ctx, const int32_t *peers_dev)
+{
+    const netmax_config &c = ctx->cfg;
+    return MixArgs{ctx->x_cur, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum, c.weight_decay};
+}
+
+// fused_peers != nullptr: the matrix-core layers apply the update to their weight columns themselves (netmax_run
+// after netmax_set_fusion); enqueue_mix then covers the remaining columns only.
+static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_t *fused_peers = nullptr)
+{
+    const netmax_config &c = ctx->cfg;
+    if (c.model == NETMAX_FLAT) {
+        launch_synth_grad(ctx->stream, c.M, c.D, c.ld, c.grad_sigma, c.seed, iter, ctx->g);
+        return check_launch(ctx, "synth_grad");
+    }
+    launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
+    const MlpPlan p = make_plan(ctx);
+    if (fused_peers) {
+        const MixArgs mx = mix_args(ctx, fused_peers);
+        launch_mlp_grad(ctx->stream, p, ctx->x_cur, ctx->g, &mx);
+    } else {
+        launch_mlp_grad(ctx->stream, p, ctx->x_cur, ctx->g);
+    }
     return check_launch(ctx, "mlp_grad");
 }
 
-static int enqueue_mix(netmax_ctx *ctx, const int32_t *peers_dev)
+static int enqueue_mix(netmax_ctx *ctx, const int32_t *peers_dev, bool fused = false)
 {
     const netmax_config &c = ctx->cfg;
-    launch_mix(ctx->stream, c.M, c.ld, ctx->x_cur, ctx->g, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum,
-               c.weight_decay);
+    if (fused)
+        launch_mix_subset(ctx->stream, c.M, ctx->d_fuse_tiles, ctx->n_fuse_tiles, ctx->fuse_skip, ctx->x_cur, ctx->g, ctx->v,
+                          ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum, c.weight_decay);
+    else
+        launch_mix(ctx->stream, c.M, c.ld, ctx->x_cur, ctx->g, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum,
+                   c.weight_decay);
     return check_launch(ctx, "mix");
 }
 
@@ -550,8 +579,8 @@ static int capture_iteration(netmax_ctx *ctx, int dir, int32_t *peers_dev)
     HIP_TRY(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
     const IterRef it{0, ctx->d_iter};
     int rc = enqueue_sample_peers(ctx, it, peers_dev);
-    if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it);
-    if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev);
+    if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
+    if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse);
     if (rc == NETMAX_OK) {
         launch_bump_iteration(ctx->stream, ctx->d_iter);
         rc = check_launch(ctx, "bump_iteration");
@@ -581,8 +610,8 @@ extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters,
         for (int32_t k = 0; k < n_iters; ++k) {
             const IterRef it{first_iter + (uint64_t)k, nullptr};
             int rc = enqueue_sample_peers(ctx, it, peers_dev);
-            if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it);
-            if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev);
+            if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
+            if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse);
             if (rc != NETMAX_OK) return rc;
             flip(ctx);
         }
@@ -603,6 +632,48 @@ extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters,
         HIP_TRY(ctx, hipGraphLaunch(ctx->graph_exec[dir], ctx->stream));
         flip(ctx);
     }
+    return NETMAX_OK;
+}
+
+// ---- the update fused into the weight-gradient kernels ---------------------------------------------------
+
+extern "C" int netmax_set_fusion(netmax_ctx *ctx, int32_t on)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    drop_graphs(ctx);
+    if (!on) { ctx->fuse = false; return NETMAX_OK; }
+    const netmax_config &c = ctx->cfg;
+    if (c.model != NETMAX_MLP) return fail(ctx, NETMAX_ESTATE, "only perceptron models have weight-gradient kernels to fuse into");
+    const MlpPlan p = make_plan(ctx);
+    MixSkip skip{};
+    for (int l = 0; l < c.n_layers; ++l)
+        if (mfma_layer_ok(p, l)) {
+            if (skip.n == MIX_MAX_SKIP) return fail(ctx, NETMAX_ESTATE, "too many layers");
+            skip.lo[skip.n] = ctx->woff[l];
+            skip.hi[skip.n] = ctx->woff[l] + (int64_t)c.dims[l] * c.dims[l + 1];
+            ++skip.n;
+        }
+    if (skip.n == 0) return fail(ctx, NETMAX_ESTATE, "no layer of this model runs on the matrix-core kernels");
+    // tiles with at least one column outside the ranges (four columns at a time, as the kernel tests them)
+    std::vector<int32_t> tiles;
+    const int64_t n_tiles = c.ld / NETMAX_TILE;
+    for (int64_t t = 0; t < n_tiles; ++t) {
+        const int64_t lo = t * NETMAX_TILE, hi = lo + NETMAX_TILE;
+        bool covered = false;
+        for (int r = 0; r < skip.n; ++r) covered |= (skip.lo[r] <= lo && hi <= skip.hi[r]);
+        if (!covered) tiles.push_back((int32_t)t);
+    }
+    (void)hipFree(ctx->d_fuse_tiles);
+    ctx->d_fuse_tiles = nullptr;
+    if (!tiles.empty()) {
+        HIP_TRY(ctx, hipMalloc(&ctx->d_fuse_tiles, tiles.size() * sizeof(int32_t)));
+        HIP_TRY(ctx, hipMemcpy(ctx->d_fuse_tiles, tiles.data(), tiles.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    }
+    ctx->n_fuse_tiles = (int)tiles.size();
+    ctx->fuse_skip = skip;
+    ctx->fuse = true;
     return NETMAX_OK;
 }
 

@@ -514,3 +514,50 @@ def test_policy_comparison_demo_runs(capsys):
     for r in runs.values():
         assert r["steps"] == int(60 * r["steps_per_time"]) and r["steps"] > 20
         assert np.isfinite(r["loss"]) and np.isfinite(r["consensus_dist"]) and r["loss"] < 2.4   # below ln 10 + margin
+
+
+@pytest.mark.parametrize("over", [dict(M=4, n_per_worker=128, dims=(256, 128, 128, 10), batch=64),
+                                  dict(M=9, n_per_worker=150, dims=(256, 256, 128, 10), batch=96),
+                                  dict(M=3, n_per_worker=100, dims=(200, 128, 128, 10), batch=64),
+                                  dict(M=2, n_per_worker=300, dims=(3072, 1024, 1024, 10))])
+def test_fused_weight_gradient_and_mix(over):
+    """netmax_run with the second-step update applied inside the weight-gradient kernels against the separate
+    kernels: the same x and v (the gradient and the update are computed by the same instructions in the same
+    order), also when replayed as a graph, and back to the separate kernels afterwards."""
+    import paper_2009_05766_amd as nm
+    w = workload("cfg5", **over)
+    inp = inputs_of(w)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        plain, fused = make_gpu(w, inp), make_gpu(w, inp)
+        nm.netmax_set_fusion(fused.ctx, True)
+        it = 0
+        for n, graph in ((3, False), (2, True), (3, True), (1, False)):
+            plain.run(it, n, use_graph=False)
+            fused.run(it, n, use_graph=graph)
+            side.synchronize()
+            it += n
+            assert np.array_equal(plain.peers.cpu().numpy(), fused.peers.cpu().numpy())
+            xa, xb = plain.get("x").cpu().numpy(), fused.get("x").cpu().numpy()
+            va, vb = plain.get("v").cpu().numpy(), fused.get("v").cpu().numpy()
+            assert np.array_equal(xa, xb), (it, float(np.abs(xa - xb).max()))
+            assert np.array_equal(va, vb), (it, float(np.abs(va - vb).max()))
+        nm.netmax_set_fusion(fused.ctx, False)
+        plain.run(it, 2)
+        fused.run(it, 2)
+        side.synchronize()
+        assert np.array_equal(plain.get("x").cpu().numpy(), fused.get("x").cpu().numpy())
+        assert np.array_equal(plain.get("g").cpu().numpy(), fused.get("g").cpu().numpy())
+        plain.close(), fused.close()
+
+
+def test_fusion_needs_matrix_core_layers():
+    import paper_2009_05766_amd as nm
+    for name, over in (("cfg3", dict(M=4, D=3000, T=5)), ("cfg1", dict())):
+        w = workload(name, **over)
+        gpu = make_gpu(w, inputs_of(w))
+        with pytest.raises(nm.NetmaxError) as e:
+            nm.netmax_set_fusion(gpu.ctx, True)
+        assert e.value.code == nm.NETMAX_ESTATE
+        nm.netmax_set_fusion(gpu.ctx, False)
+        gpu.close()
