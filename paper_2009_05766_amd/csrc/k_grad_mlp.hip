@@ -307,18 +307,21 @@ softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const in
     }
 }
 
-// db = column sums of dZ; thread per (worker, output).
+// db = column sums of dZ.  One workgroup = one worker x 64 outputs; the batch rows are dealt to four groups of
+// threads (rows r, r + 4, ...), whose partial sums are added in the order of the groups.
 __global__ void __launch_bounds__(256)
 bias_grad_kernel(int M, int B, int64_t dout, const float *__restrict__ dz, int64_t boff,
                  float *__restrict__ G)
 {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)M * dout) return;
-    const int g = (int)(t / dout);
-    const int64_t c = t - (int64_t)g * dout;
+    __shared__ float part[4][64];
+    const int g = blockIdx.y, lane_c = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 64 + lane_c;
     float s = 0.0f;
-    for (int b = 0; b < B; ++b) s += dz[((size_t)g * B + b) * dout + c];
-    G[tiled_offset(M, g, boff + c)] = s;
+    if (c < dout)
+        for (int b = rg; b < B; b += 4) s += dz[((size_t)g * B + b) * dout + c];
+    part[rg][lane_c] = s;
+    __syncthreads();
+    if (rg == 0 && c < dout) G[tiled_offset(M, g, boff + c)] = ((part[0][lane_c] + part[1][lane_c]) + part[2][lane_c]) + part[3][lane_c];
 }
 
 void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, const MixArgs *fuse)
@@ -381,9 +384,8 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
             launch_gemm(s, wg, wg.in.kind, p.M, din, dout);
         }
         if (!bias_done[l]) {
-            const int64_t nb = (int64_t)p.M * dout;
-            hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s, p.M, p.B, dout,
-                               p.dz[cur], p.woff[l] + din * dout, G);
+            hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((dout + 63) / 64), (unsigned)p.M), dim3(256), 0, s, p.M, p.B,
+                               dout, p.dz[cur], p.woff[l] + din * dout, G);
         }
         if (l > 0) {
             if (fast[l]) {
