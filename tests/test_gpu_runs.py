@@ -12,9 +12,11 @@ pytestmark = pytest.mark.gpu
 TOL_STEP, TOL_RUN = 1e-5, 1e-4
 
 
-def _sync_oracle_from_gpu(gpu, o):
-    o.X[:] = gpu.get("x").cpu().numpy()
-    o.V[:] = gpu.get("v").cpu().numpy()
+def _sync_gpu_from_oracle(gpu, o):
+    """The GPU run takes over the oracle's state (never the other way round: what the oracle computes depends on
+    nothing the library produced)."""
+    gpu.set("x", o.X)
+    gpu.set("v", o.V)
 
 
 def _free_run(w, T, ora_threads=8, cd_rel=1e-3):
@@ -46,7 +48,7 @@ def _stepwise(w, T, tol, ora_threads=8):
     gpu, o = make_gpu(w, inp), make_oracle(w, inp)
     worst = 0.0
     for it in range(T):
-        _sync_oracle_from_gpu(gpu, o)
+        _sync_gpu_from_oracle(gpu, o)
         gpu.step(it)
         peer = o.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), peer)
@@ -58,8 +60,8 @@ def _stepwise(w, T, tol, ora_threads=8):
 
 
 def _windows(w, T, K, tol, ora_threads=8, operands_bf16=False):
-    """The whole horizon T in windows of K steps: at the start of each window the oracle takes over the
-    GPU's state, then both run K steps freely.  Needed for ReLU networks: a hidden pre-activation within
+    """The whole horizon T in windows of K steps: at the start of each window the GPU run takes over the
+    oracle's state, then both run K steps freely.  Needed for ReLU networks: a hidden pre-activation within
     rounding distance of zero gets derivative 0 on one side and 1 on the other, a discontinuous change of
     the gradient (about 1/sqrt(batch * active units) of its norm) that no summation order can avoid and
     that the dynamics then amplify.  Returns the worst end-of-window error."""
@@ -70,7 +72,7 @@ def _windows(w, T, K, tol, ora_threads=8, operands_bf16=False):
     worst = 0.0
     for it in range(T):
         if it % K == 0:
-            _sync_oracle_from_gpu(gpu, o)
+            _sync_gpu_from_oracle(gpu, o)
         gpu.step(it)
         peer = o.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), peer)
@@ -135,7 +137,7 @@ def test_cfg5_reduced_shape():
 def test_cfg5_all_workers_tiny_layers_full_T():
     w = workload("cfg5", n_per_worker=64, dims=(48, 32, 16, 10), batch=16)
     assert _windows(w, w.T, 5, TOL_RUN_BF16_SAME, operands_bf16=True) < TOL_RUN_BF16_SAME
-    assert _windows(w, w.T, 50, TOL_BF16) < TOL_BF16             # against exact arithmetic
+    assert _windows(w, w.T, 25, TOL_BF16) < TOL_BF16             # against exact arithmetic
     err, cd0, cd = _free_run(w, w.T, cd_rel=0.2)
     print(f"cfg5 tiny layers, free run of {w.T} steps against exact arithmetic: relative error {err:.3e}")
     assert err < 0.1, err           # sanity only: operand rounding plus ReLU kinks over 500 free steps
@@ -475,7 +477,7 @@ def test_async_schedule_perceptron(name, over):
     peers = torch.zeros(n, dtype=torch.int32, device="cuda")
     worst = 0.0
     for k0 in range(0, n, 6):                       # windows: re-synchronised so that ReLU flips do not accumulate
-        o.X[:], o.V[:] = gpu.get("x").cpu().numpy(), gpu.get("v").cpu().numpy()
+        _sync_gpu_from_oracle(gpu, o)
         nm.netmax_async_run(gpu.ctx, k0, 6, active[k0:], peers[k0:])
         want = np.array([o.async_step(k) for k in range(k0, k0 + 6)], dtype=np.int32)
         assert np.array_equal(active[k0:k0 + 6].cpu().numpy(), want[:, 0])
