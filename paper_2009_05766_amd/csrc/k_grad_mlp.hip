@@ -41,7 +41,27 @@ struct LayerInput {
         if constexpr (KIND == IN_GATHER_BF16 || KIND == IN_ACT_BF16) return as_float(u << 16);
         else return maybe_round(as_float(u), round);
     }
+    // the same element as bits(): element index of feature 0 of batch row r, and the load of index + k
+    template <int KIND> __device__ __forceinline__ int64_t row_index(int g, int r, const int64_t *rows) const
+    {
+        if constexpr (KIND == IN_GATHER_F32 || KIND == IN_GATHER_BF16) return rows[r] * din;
+        else return ((int64_t)g * B + r) * din;
+    }
+    template <int KIND> __device__ __forceinline__ uint32_t load_index(int64_t index) const
+    {
+        if constexpr (KIND == IN_GATHER_F32) return ((const uint32_t *)feats)[index];
+        else if constexpr (KIND == IN_GATHER_BF16) return ((const uint16_t *)feats)[index];
+        else if constexpr (KIND == IN_ACT_F32) return ((const uint32_t *)act_prev)[index];
+        else return act_prev_bf16[index];
+    }
 };
+
+// tiled_offset() with one 32 x 32 -> 64 bit multiply-add: j + (((j >> 11) (M - 1) + i) << 11); needs j < 2^43
+__device__ __forceinline__ size_t tiled_offset_quick(int M, int i, int64_t j)
+{
+    const uint64_t t = (uint64_t)(uint32_t)(j >> TILE_SHIFT) * (uint32_t)(M - 1) + (uint32_t)i;
+    return (size_t)j + (size_t)(t << TILE_SHIFT);
+}
 
 // Z = A W + b, optional ReLU.  rows = batch, cols = dout, K = din.
 struct FwdProblem {
@@ -62,6 +82,14 @@ struct FwdProblem {
         return ((const uint32_t *)X)[tiled_offset(M, g, woff + k * dout + c)];
     }
     __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    // the operands as base + k * step: what does not depend on the contraction index is computed once per thread
+    static constexpr bool A_AFFINE = true;
+    template <int AK> __device__ int64_t a_base(int g, int64_t r, const int64_t *rows) const { return in.row_index<AK>(g, (int)r, rows); }
+    __device__ int64_t a_step() const { return 1; }
+    template <int AK> __device__ uint32_t a_at(int64_t index) const { return in.load_index<AK>(index); }
+    __device__ int64_t b_base(int g, int64_t c) const { return woff + c; }
+    __device__ int64_t b_step() const { return dout; }
+    __device__ uint32_t b_at(int g, int64_t index) const { return ((const uint32_t *)X)[tiled_offset_quick(M, g, index)]; }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
         float z = acc + X[tiled_offset(M, g, woff + din * dout + c)];
@@ -94,6 +122,13 @@ struct DgradProblem {
         return ((const uint32_t *)X)[tiled_offset(M, g, woff + c * dout + k)];
     }
     __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    static constexpr bool A_AFFINE = true;
+    template <int AK> __device__ int64_t a_base(int g, int64_t r, const int64_t *) const { return ((int64_t)g * B + r) * dout; }
+    __device__ int64_t a_step() const { return 1; }
+    template <int AK> __device__ uint32_t a_at(int64_t index) const { return ((const uint32_t *)dz)[index]; }
+    __device__ int64_t b_base(int g, int64_t c) const { return woff + c * dout; }
+    __device__ int64_t b_step() const { return 1; }
+    __device__ uint32_t b_at(int g, int64_t index) const { return ((const uint32_t *)X)[tiled_offset_quick(M, g, index)]; }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
         const size_t q = ((size_t)g * B + r) * din + c;
@@ -126,6 +161,13 @@ struct WgradProblem {
         return ((const uint32_t *)dz)[((size_t)g * B + k) * dout + c];
     }
     __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    static constexpr bool A_AFFINE = false;      // the batch row of contraction index k is looked up (gathered data)
+    template <int AK> __device__ int64_t a_base(int, int64_t, const int64_t *) const { return 0; }
+    __device__ int64_t a_step() const { return 0; }
+    template <int AK> __device__ uint32_t a_at(int64_t) const { return 0u; }
+    __device__ int64_t b_base(int g, int64_t c) const { return (int64_t)g * B * dout + c; }
+    __device__ int64_t b_step() const { return dout; }
+    __device__ uint32_t b_at(int, int64_t index) const { return ((const uint32_t *)dz)[index]; }
     __device__ void store(int g, int64_t r, int64_t c, float acc) const
     {
         G[tiled_offset(M, g, woff + r * dout + c)] = acc;
@@ -158,6 +200,26 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
     constexpr int A_PER = (TM * TK) / GEMM_THREADS, B_PER = (TN * TK) / GEMM_THREADS;
     uint32_t ra[A_PER], rb[B_PER];
     unsigned a_ok = 0, b_ok = 0;          // bit q: element q of the fetch lies inside the operand
+    // per element of a fetch: its index at contraction index 0 (row / column clamped into the operand)
+    int64_t a_idx0[A_PER], b_idx0[B_PER];
+    unsigned a_in = 0, b_in = 0;          // bit q: the row / column of element q exists
+#pragma unroll
+    for (int q = 0; q < A_PER; ++q) {
+        const int e = tid + q * GEMM_THREADS;
+        const int r = Problem::A_K_FAST ? e / TK : e % TM;
+        const int64_t rr = row0 + r;
+        a_in |= (unsigned)(rr < R) << q;
+        a_idx0[q] = Problem::A_AFFINE ? p.template a_base<AK>(g, rr < R ? rr : R - 1, s_rows) : 0;
+    }
+#pragma unroll
+    for (int q = 0; q < B_PER; ++q) {
+        const int e = tid + q * GEMM_THREADS;
+        const int c = Problem::B_C_FAST ? e % TN : e / TK;
+        const int64_t cc = col0 + c;
+        b_in |= (unsigned)(cc < C) << q;
+        b_idx0[q] = p.b_base(g, cc < C ? cc : C - 1);
+    }
+    const int64_t a_step = p.a_step(), b_step = p.b_step();
     auto fetch = [&](int64_t k0) {
         a_ok = b_ok = 0;
 #pragma unroll
@@ -165,18 +227,22 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
             const int e = tid + q * GEMM_THREADS;
             int kk, r;
             if (Problem::A_K_FAST) { kk = e % TK; r = e / TK; } else { r = e % TM; kk = e / TM; }
-            const int64_t rr = row0 + r, kq = k0 + kk;
-            a_ok |= (unsigned)(rr < R && kq < K) << q;
-            ra[q] = p.template a_bits<AK>(g, rr < R ? rr : R - 1, kq < K ? kq : K - 1, s_rows);
+            const int64_t kq = k0 + kk, kc = kq < K ? kq : K - 1;
+            a_ok |= (unsigned)(((a_in >> q) & 1u) && kq < K) << q;
+            if constexpr (Problem::A_AFFINE) {
+                ra[q] = p.template a_at<AK>(a_idx0[q] + kc * a_step);
+            } else {
+                const int64_t rr = row0 + r;
+                ra[q] = p.template a_bits<AK>(g, rr < R ? rr : R - 1, kc, s_rows);
+            }
         }
 #pragma unroll
         for (int q = 0; q < B_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
-            int kk, c;
-            if (Problem::B_C_FAST) { c = e % TN; kk = e / TN; } else { kk = e % TK; c = e / TK; }
-            const int64_t cc = col0 + c, kq = k0 + kk;
-            b_ok |= (unsigned)(cc < C && kq < K) << q;
-            rb[q] = p.b_bits(g, kq < K ? kq : K - 1, cc < C ? cc : C - 1);
+            const int kk = Problem::B_C_FAST ? e / TN : e % TK;
+            const int64_t kq = k0 + kk, kc = kq < K ? kq : K - 1;
+            b_ok |= (unsigned)(((b_in >> q) & 1u) && kq < K) << q;
+            rb[q] = p.b_at(g, b_idx0[q] + kc * b_step);
         }
     };
     gemm_acc acc;
