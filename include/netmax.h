@@ -175,8 +175,10 @@ int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *p
  * computes it reads x, v and the peer's x and writes x' and v' of those columns directly (Algorithm 2's two update
  * steps on the gradient while it is still in registers).  A reduced mix covers all other columns.  x' and v' are
  * the same as without fusion; g then holds only the columns the fused kernels do not cover.  on = 0 switches back.
- * Affects netmax_run only (netmax_local_step and netmax_mix stay separate steps).  NETMAX_ESTATE for flat models
- * and for models without such a layer.  Waits for the stream and drops captured graphs. */
+ * For flat models the fused variant generates the synthetic gradient inside the update kernel (g is still written,
+ * with the same values; its read by the update is what is saved).
+ * Affects netmax_run only (netmax_local_step and netmax_mix stay separate steps).  NETMAX_ESTATE for perceptron
+ * models without such a layer.  Waits for the stream and drops captured graphs. */
 int netmax_set_fusion(netmax_ctx *ctx, int32_t on);
 
 /* ---- Asynchronous schedule (Section II-B, Eq. (c2)-(c4)) ----------------------------------------------------

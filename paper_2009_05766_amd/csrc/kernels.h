@@ -41,6 +41,11 @@ void prepare_kernels();
 void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float *G, float *V, float *Xnext,
                 const int32_t *peer, const float *w, float alpha, float mu, float wd);
 
+// Flat models: the synthetic gradient generated inside the update (g is still written).
+void launch_mix_synth(hipStream_t s, int M, int64_t D, int64_t ld, const float *Xcur, float *G, float *V, float *Xnext,
+                      const int32_t *peer, const float *w, float alpha, float mu, float wd, float sigma, uint64_t seed,
+                      const IterRef &iter);
+
 // The same update for a list of column tiles only, leaving out up to MIX_MAX_SKIP column ranges (multiples of four
 // columns) that another kernel has already updated.  tiles: device [n_tiles_listed].
 constexpr int MIX_MAX_SKIP = 8;

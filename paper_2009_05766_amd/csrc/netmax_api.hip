@@ -500,6 +500,7 @@ static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_
 {
     const netmax_config &c = ctx->cfg;
     if (c.model == NETMAX_FLAT) {
+        if (fused_peers) return NETMAX_OK;           // the fused update generates the gradient itself
         launch_synth_grad(ctx->stream, c.M, c.D, c.ld, c.grad_sigma, c.seed, iter, ctx->g);
         return check_launch(ctx, "synth_grad");
     }
@@ -514,10 +515,13 @@ static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_
     return check_launch(ctx, "mlp_grad");
 }
 
-static int enqueue_mix(netmax_ctx *ctx, const int32_t *peers_dev, bool fused = false)
+static int enqueue_mix(netmax_ctx *ctx, const int32_t *peers_dev, bool fused = false, const IterRef &iter = IterRef{0, nullptr})
 {
     const netmax_config &c = ctx->cfg;
-    if (fused)
+    if (fused && c.model == NETMAX_FLAT)
+        launch_mix_synth(ctx->stream, c.M, c.D, c.ld, ctx->x_cur, ctx->g, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr,
+                         c.momentum, c.weight_decay, c.grad_sigma, c.seed, iter);
+    else if (fused)
         launch_mix_subset(ctx->stream, c.M, ctx->d_fuse_tiles, ctx->n_fuse_tiles, ctx->fuse_skip, ctx->x_cur, ctx->g, ctx->v,
                           ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum, c.weight_decay);
     else
@@ -580,7 +584,7 @@ static int capture_iteration(netmax_ctx *ctx, int dir, int32_t *peers_dev)
     const IterRef it{0, ctx->d_iter};
     int rc = enqueue_sample_peers(ctx, it, peers_dev);
     if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
-    if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse);
+    if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse, it);
     if (rc == NETMAX_OK) {
         launch_bump_iteration(ctx->stream, ctx->d_iter);
         rc = check_launch(ctx, "bump_iteration");
@@ -611,7 +615,7 @@ extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters,
             const IterRef it{first_iter + (uint64_t)k, nullptr};
             int rc = enqueue_sample_peers(ctx, it, peers_dev);
             if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
-            if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse);
+            if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse, it);
             if (rc != NETMAX_OK) return rc;
             flip(ctx);
         }
@@ -645,7 +649,10 @@ extern "C" int netmax_set_fusion(netmax_ctx *ctx, int32_t on)
     drop_graphs(ctx);
     if (!on) { ctx->fuse = false; return NETMAX_OK; }
     const netmax_config &c = ctx->cfg;
-    if (c.model != NETMAX_MLP) return fail(ctx, NETMAX_ESTATE, "only perceptron models have weight-gradient kernels to fuse into");
+    if (c.model == NETMAX_FLAT) {                    // the gradient generator moves into the update kernel
+        ctx->fuse = true;
+        return NETMAX_OK;
+    }
     const MlpPlan p = make_plan(ctx);
     MixSkip skip{};
     for (int l = 0; l < c.n_layers; ++l)

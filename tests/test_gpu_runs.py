@@ -555,14 +555,39 @@ def test_fused_weight_gradient_and_mix(over):
 
 def test_fusion_needs_matrix_core_layers():
     import paper_2009_05766_amd as nm
-    for name, over in (("cfg3", dict(M=4, D=3000, T=5)), ("cfg1", dict())):
-        w = workload(name, **over)
-        gpu = make_gpu(w, inputs_of(w))
-        with pytest.raises(nm.NetmaxError) as e:
-            nm.netmax_set_fusion(gpu.ctx, True)
-        assert e.value.code == nm.NETMAX_ESTATE
-        nm.netmax_set_fusion(gpu.ctx, False)
-        gpu.close()
+    w = workload("cfg1")
+    gpu = make_gpu(w, inputs_of(w))
+    with pytest.raises(nm.NetmaxError) as e:
+        nm.netmax_set_fusion(gpu.ctx, True)
+    assert e.value.code == nm.NETMAX_ESTATE
+    nm.netmax_set_fusion(gpu.ctx, False)
+    gpu.close()
+
+
+@pytest.mark.parametrize("name,over", [("cfg3", dict(M=16, D=50000)), ("cfg4", dict(M=5, D=9000))])
+def test_fused_synthetic_gradient_and_mix(name, over):
+    """Flat models: the gradient generated inside the update kernel.  g, x and v equal those of the two separate
+    kernels bit for bit, eagerly and as a graph; the oracle agrees as for the separate kernels."""
+    import paper_2009_05766_amd as nm
+    w = workload(name, **over)
+    inp = inputs_of(w)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        plain, fused, o = make_gpu(w, inp), make_gpu(w, inp), make_oracle(w, inp)
+        nm.netmax_set_fusion(fused.ctx, True)
+        it = 0
+        for n, graph in ((3, False), (4, True), (2, False)):
+            plain.run(it, n)
+            fused.run(it, n, use_graph=graph)
+            side.synchronize()
+            for k in range(n):
+                o.step(it + k)
+            it += n
+            for name_ in ("x", "v", "g"):
+                assert np.array_equal(plain.get(name_).cpu().numpy(), fused.get(name_).cpu().numpy()), (it, name_)
+        assert rel_err_rows(fused.get("x").cpu().numpy(), o.X) < TOL_RUN
+        assert np.all(fused.get("g").cpu().numpy()[:, w.D:] == 0)
+        plain.close(), fused.close()
 
 
 def test_fused_update_with_weight_decay_fixed_weight_and_policy_change():
