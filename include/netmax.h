@@ -210,6 +210,12 @@ int netmax_async_run(netmax_ctx *ctx, uint64_t first_step, uint64_t n_steps, int
 int netmax_update_times(netmax_ctx *ctx, const int32_t *peers_dev, const float *t_dev, float beta, float *ema_dev,
                         float *clock_dev);
 
+/* The same bookkeeping for global steps of the asynchronous schedule, taken in order: for s = 0 .. n_steps - 1 with
+ * i = active_dev[s], m = peers_dev[s]: ema_dev[i][m] = beta ema_dev[i][m] + (1 - beta) t_dev[i][m] (not for m = i),
+ * clock_dev[i] += t_dev[i][m].  active_dev, peers_dev: device int32 [n_steps], as netmax_async_run fills them. */
+int netmax_update_times_async(netmax_ctx *ctx, const int32_t *active_dev, const int32_t *peers_dev, uint64_t n_steps,
+                              const float *t_dev, float beta, float *ema_dev, float *clock_dev);
+
 /* Consensus distance sum_i ||x_i - mean_i x_i||^2 over the first D columns of the current parameters: the
  * complete-graph form of the model-difference penalty of Eq. (1).  fp64 accumulation, fixed summation
  * order.  Waits for the stream; out_host: host double. */

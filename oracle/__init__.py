@@ -215,6 +215,15 @@ def update_times(peer: np.ndarray, t: np.ndarray, beta: float, ema: np.ndarray, 
                            _p(_chk(ema, np.float32)), _p(None if clock is None else _chk(clock, np.float32)))
 
 
+def update_times_async(active: np.ndarray, peers: np.ndarray, t: np.ndarray, beta: float, ema: np.ndarray,
+                       clock: Optional[np.ndarray] = None):
+    """UpdateTimeVector for a run of global steps of the asynchronous schedule (in order)."""
+    M = t.shape[0]
+    lib().ora_update_times_async(C.c_int(M), C.c_int64(active.shape[0]), _p(_chk(active, np.int32)), _p(_chk(peers, np.int32)),
+                                 _p(_chk(t, np.float32)), C.c_double(beta), _p(_chk(ema, np.float32)),
+                                 _p(None if clock is None else _chk(clock, np.float32)))
+
+
 def consensus_dist(X: np.ndarray, D: Optional[int] = None) -> float:
     M, ld = X.shape
     return float(lib().ora_consensus_dist(C.c_int(M), C.c_int64(ld if D is None else D), C.c_int64(ld),

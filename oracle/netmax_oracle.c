@@ -474,6 +474,19 @@ void ora_update_times(int M, const int32_t *peer, const float *t, double beta, f
     }
 }
 
+/* The same bookkeeping for the asynchronous schedule: the global steps are taken in order, step s concerns only its
+ * active worker active[s] and the peer peers[s] it pulled from. */
+void ora_update_times_async(int M, int64_t n_steps, const int32_t *active, const int32_t *peers, const float *t,
+                            double beta, float *ema, float *clock)
+{
+    for (int64_t s = 0; s < n_steps; ++s) {
+        const int32_t i = active[s], m = peers[s];
+        const size_t e = (size_t)i * M + m;
+        if (m != i) ema[e] = (float)(beta * (double)ema[e] + (1.0 - beta) * (double)t[e]);
+        if (clock) clock[i] = (float)((double)clock[i] + (double)t[e]);
+    }
+}
+
 /* ------------------------------------------------------------------ consensus distance
  * CD = sum_i || x_i - xbar ||^2, xbar = (1/M) sum_i x_i, over the first D columns: the
  * complete-graph form of the model-difference penalty of Eq. (1)

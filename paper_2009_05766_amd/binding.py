@@ -22,7 +22,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_activity", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_update_times_async", "netmax_activity", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
     "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -79,6 +79,7 @@ def load():
         "netmax_mix": (C.c_int, [vp, u64, vp]),
         "netmax_run": (C.c_int, [vp, u64, i32, vp, i32]),
         "netmax_update_times": (C.c_int, [vp, vp, vp, f32, vp, vp]),
+        "netmax_update_times_async": (C.c_int, [vp, vp, vp, C.c_uint64, vp, f32, vp, vp]),
         "netmax_set_fusion": (C.c_int, [vp, i32]),
         "netmax_activity": (C.c_int, [C.c_int32, vp, vp, vp, vp]),
         "netmax_set_activity": (C.c_int, [vp, vp]),
@@ -263,6 +264,13 @@ def netmax_update_times(ctx, peers, t, beta: float, ema, clock=None):
     import torch
     _check(load().netmax_update_times(ctx, _dp(peers, torch.int32), _dp(t, torch.float32), beta, _dp(ema, torch.float32),
                                       None if clock is None else _dp(clock, torch.float32)), ctx)
+
+
+def netmax_update_times_async(ctx, active, peers, n_steps: int, t, beta: float, ema, clock=None):
+    import torch
+    _check(load().netmax_update_times_async(ctx, _dp(active, torch.int32), _dp(peers, torch.int32), n_steps,
+                                            _dp(t, torch.float32), beta, _dp(ema, torch.float32),
+                                            None if clock is None else _dp(clock, torch.float32)), ctx)
 
 
 def netmax_consensus_dist(ctx) -> float:

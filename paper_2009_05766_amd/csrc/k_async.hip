@@ -67,6 +67,33 @@ __global__ void __launch_bounds__(256) async_row_kernel(int M, int64_t D, float 
     }
 }
 
+// Time bookkeeping (Algorithm 2, UpdateTimeVector) for a run of global steps: one thread per worker walks the steps in
+// order and handles those in which it is the active worker, so every worker's entries change in step order.
+__global__ void __launch_bounds__(256) async_times_kernel(int M, int64_t n_steps, const int32_t *__restrict__ active,
+                                                          const int32_t *__restrict__ peers, const float *__restrict__ t,
+                                                          float beta, float *__restrict__ ema, float *__restrict__ clock)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    float c = clock ? clock[i] : 0.0f;
+    for (int64_t s = 0; s < n_steps; ++s) {
+        if (active[s] != i) continue;
+        int m = peers[s];
+        if ((unsigned)m >= (unsigned)M) m = i;
+        const size_t e = (size_t)i * M + m;
+        const float tim = t[e];
+        if (m != i) ema[e] = fmaf(beta, ema[e], (1.0f - beta) * tim);
+        c += tim;
+    }
+    if (clock) clock[i] = c;
+}
+
+void launch_async_times(hipStream_t s, int M, int64_t n_steps, const int32_t *active, const int32_t *peers, const float *t,
+                        float beta, float *ema, float *clock)
+{
+    hipLaunchKernelGGL(async_times_kernel, dim3((M + 255) / 256), dim3(256), 0, s, M, n_steps, active, peers, t, beta, ema, clock);
+}
+
 void launch_async_draw(hipStream_t s, int M, const uint32_t *act_thr, int act_last, const uint32_t *thr, const int32_t *last,
                        uint64_t seed, uint64_t first, uint64_t n_steps, int32_t *active, int32_t *peers)
 {

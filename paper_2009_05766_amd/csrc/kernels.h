@@ -27,6 +27,9 @@ void launch_async_row(hipStream_t s, bool synth, int M, int64_t D, int64_t ld, f
                       const int32_t *active, const int32_t *peers, const float *w, float alpha, float mu, float wd,
                       float sigma, uint64_t seed, uint64_t k);
 
+void launch_async_times(hipStream_t s, int M, int64_t n_steps, const int32_t *active, const int32_t *peers, const float *t,
+                        float beta, float *ema, float *clock);
+
 // Iteration-time bookkeeping of Algorithm 2 (UpdateTimeVector) against a given time matrix.
 void launch_update_times(hipStream_t s, int M, const int32_t *peer, const float *t, float beta, float *ema, float *clock);
 

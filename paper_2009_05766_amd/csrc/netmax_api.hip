@@ -775,6 +775,17 @@ extern "C" int netmax_update_times(netmax_ctx *ctx, const int32_t *peers_dev, co
     return check_launch(ctx, "update_times");
 }
 
+extern "C" int netmax_update_times_async(netmax_ctx *ctx, const int32_t *active_dev, const int32_t *peers_dev, uint64_t n_steps,
+                                         const float *t_dev, float beta, float *ema_dev, float *clock_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (!active_dev || !peers_dev || !t_dev || !ema_dev || !(beta >= 0.0f) || !(beta <= 1.0f) || n_steps > (1ull << 31))
+        return fail(ctx, NETMAX_EINVAL, "NULL pointer, beta outside [0, 1] or more than 2^31 steps");
+    if (n_steps == 0) return NETMAX_OK;
+    launch_async_times(ctx->stream, ctx->cfg.M, (int64_t)n_steps, active_dev, peers_dev, t_dev, beta, ema_dev, clock_dev);
+    return check_launch(ctx, "update_times_async");
+}
+
 extern "C" int netmax_consensus_dist(netmax_ctx *ctx, double *out_host)
 {
     if (!ctx) return NETMAX_EINVAL;

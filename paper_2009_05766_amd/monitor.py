@@ -39,6 +39,10 @@ class Monitor:
         B.netmax_update_times(self.run.ctx, self.run.peers if peers is None else peers, self.times, self.beta,
                               self.ema, self.clock)
 
+    def observe_async(self, active, peers, n_steps: int):
+        """The same bookkeeping for a run of global steps of the asynchronous schedule (netmax_async_run's output)."""
+        B.netmax_update_times_async(self.run.ctx, active, peers, n_steps, self.times, self.beta, self.ema, self.clock)
+
     def collect(self) -> np.ndarray:
         """The matrix of smoothed iteration times the monitor gathers from the workers (Algorithm 1)."""
         import torch

@@ -487,6 +487,29 @@ def test_async_schedule_perceptron(name, over):
     gpu.close()
 
 
+def test_async_time_bookkeeping_matches_oracle():
+    import oracle
+    import paper_2009_05766_amd as nm
+    from netmax_inputs import iteration_times
+    w = workload("cfg3", M=8, D=3000, T=5)
+    inp = inputs_of(w)
+    gpu, o = _async_pair(w, inp)
+    n, beta = 300, 0.7
+    t = iteration_times(w.links, w.M).astype(np.float32)
+    active = torch.zeros(n, dtype=torch.int32, device="cuda")
+    peers = torch.zeros(n, dtype=torch.int32, device="cuda")
+    nm.netmax_async_run(gpu.ctx, 0, n, active, peers)
+    ema = torch.zeros((w.M, w.M), dtype=torch.float32, device="cuda")
+    clock = torch.zeros(w.M, dtype=torch.float32, device="cuda")
+    nm.netmax_update_times_async(gpu.ctx, active, peers, n, torch.from_numpy(t).cuda(), beta, ema, clock)
+    want = np.array([oracle.async_draw(o.Tact, o.last_act, o.T, o.last, o.seed, k) for k in range(n)], dtype=np.int32)
+    ema_o, clock_o = np.zeros((w.M, w.M), np.float32), np.zeros(w.M, np.float32)
+    oracle.update_times_async(np.ascontiguousarray(want[:, 0]), np.ascontiguousarray(want[:, 1]), t, beta, ema_o, clock_o)
+    assert np.allclose(ema.cpu().numpy(), ema_o, rtol=1e-6, atol=0) and np.allclose(clock.cpu().numpy(), clock_o, rtol=1e-5)
+    assert np.count_nonzero(ema_o) > w.M
+    gpu.close()
+
+
 def test_async_schedule_needs_activities():
     import paper_2009_05766_amd as nm
     w = workload("cfg3", M=4, D=3000, T=5)
@@ -516,6 +539,20 @@ def test_policy_comparison_demo_runs(capsys):
     for r in runs.values():
         assert r["steps"] == int(60 * r["steps_per_time"]) and r["steps"] > 20
         assert np.isfinite(r["loss"]) and np.isfinite(r["consensus_dist"]) and r["loss"] < 2.4   # below ln 10 + margin
+
+
+def test_dynamic_network_demo_runs(capsys):
+    """The moving-slow-link demonstration: the monitor loop on the asynchronous schedule regenerates policies from
+    the smoothed times the workers saw and installs them, the fixed uniform policy generates none, both train."""
+    import json
+    from paper_2009_05766_amd import demo_policies
+    assert demo_policies.main(["--workload", "cfg1", "--dynamic", "3", "--time", "40", "--periods", "2",
+                               "--K", "20", "--R", "6"]) == 0
+    runs = json.loads(capsys.readouterr().out)["runs"]
+    fixed, loop = runs["uniform policy, fixed"], runs["monitor loop (Algorithms 1-3)"]
+    assert fixed["policies_generated"] == 0 and 1 <= loop["policies_generated"] <= 6
+    for r in (fixed, loop):
+        assert r["steps"] > 20 and np.isfinite(r["loss"]) and np.isfinite(r["consensus_dist"]) and r["loss"] < 2.4
 
 
 @pytest.mark.parametrize("over", [dict(M=4, n_per_worker=128, dims=(256, 128, 128, 10), batch=64),

@@ -111,3 +111,30 @@ def test_one_step_second_moment_matches_Y_P(ora):
     want = np.einsum("ic,ij,jc->c", xs, Y, xs)
     assert np.all(np.abs(mean - want) < 5 * sd + 1e-9 * np.abs(want))
     assert np.all(sd > 0)
+
+
+def test_async_time_bookkeeping(ora):
+    """UpdateTimeVector over a run of global steps: the same as handling the steps one by one with the synchronous
+    routine restricted to the active worker, and the geometric closed form for a repeated pair."""
+    rng = np.random.default_rng(3)
+    M, n, beta = 5, 200, 0.6
+    t = rng.uniform(0.5, 4.0, (M, M)).astype(np.float32)
+    active = rng.integers(0, M, n).astype(np.int32)
+    peers = rng.integers(0, M, n).astype(np.int32)
+    ema, clock = np.zeros((M, M), np.float32), np.zeros(M, np.float32)
+    ora.update_times_async(active, peers, t, beta, ema, clock)
+    ema2, clock2 = np.zeros((M, M), np.float32), np.zeros(M, np.float32)
+    for s in range(n):
+        # the synchronous routine with every worker but the active one "selecting itself" at zero cost
+        peer_all = np.arange(M, dtype=np.int32)
+        peer_all[active[s]] = peers[s]
+        t_step = t.copy()
+        idle = np.arange(M) != active[s]
+        t_step[idle, idle] = 0.0
+        ora.update_times(peer_all, t_step, beta, ema2, clock2)
+    assert np.array_equal(ema, ema2) and np.allclose(clock, clock2, rtol=1e-6)
+    # one pair visited k times: (1 - beta^k) t
+    k = 9
+    ema3 = np.zeros((M, M), np.float32)
+    ora.update_times_async(np.full(k, 2, np.int32), np.full(k, 4, np.int32), t, beta, ema3, None)
+    assert abs(ema3[2, 4] - (1 - beta ** k) * t[2, 4]) < 1e-5 and np.count_nonzero(ema3) == 1
