@@ -581,6 +581,11 @@ def test_fused_weight_gradient_and_mix(over):
             va, vb = plain.get("v").cpu().numpy(), fused.get("v").cpu().numpy()
             assert np.array_equal(xa, xb), (it, float(np.abs(xa - xb).max()))
             assert np.array_equal(va, vb), (it, float(np.abs(va - vb).max()))
+        if w.D < 1 << 18:                                   # and against the oracle directly, as for the separate kernels
+            o = make_oracle(w, inp)
+            for k in range(it):
+                o.step(k)
+            assert rel_err_rows(xb, o.X) < TOL_BF16
         nm.netmax_set_fusion(fused.ctx, False)
         plain.run(it, 2)
         fused.run(it, 2)
