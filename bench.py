@@ -82,8 +82,19 @@ def cpu_baseline(w, inp, budget_s: float = 12.0):
     for it in range(1, 1 + iters):
         o.step(it)
     dt = (time.perf_counter() - t0) / iters
+    # the same oracle with its loop over workers spread over the host's threads (same results: every worker reads
+    # the previous iteration's copies only), reported beside the single-thread figure
+    threads = max(1, min(16, os.cpu_count() or 1, o.M))          # one worker per thread at most
+    oracle.set_threads(threads)
+    iters_mt = max(1, min(int(0.5 * budget_s / max(dt, 1e-9)), 50))
+    t0 = time.perf_counter()
+    for it in range(1 + iters, 1 + iters + iters_mt):
+        o.step(it)
+    dt_mt = (time.perf_counter() - t0) / iters_mt
+    oracle.set_threads(1)
     return {"value": w.M / (dt * scale), "unit": "worker-iterations/s", "cores": 1, "kind": "oracle",
-            "sample": f"{sample}, {iters} iterations timed, scaled to the whole workload"}
+            "sample": f"{sample}, {iters} iterations timed, scaled to the whole workload",
+            "all_threads": {"value": w.M / (dt_mt * scale), "cores": threads, "iterations": iters_mt}}
 
 
 def main() -> int:
