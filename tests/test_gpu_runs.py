@@ -205,8 +205,11 @@ def test_flat_full_shape_sampled_columns(name):
                last_tile, w.D - 256]
     width = 256
     oracles = []
+    tiles_view = gpu.x_a.view(ld // TILE, M, TILE)          # the documented layout, read with torch alone
     for c0 in windows:
-        x0 = gpu.get_window("x", c0, width).cpu().numpy().copy()
+        cols = torch.arange(c0, c0 + width, device=gpu.x_a.device)
+        x0 = tiles_view[cols // TILE, :, cols % TILE].T.contiguous().cpu().numpy()   # no library kernel touches the oracle's input
+        assert np.array_equal(x0, gpu.get_window("x", c0, width).cpu().numpy())
         valid = min(width, w.D - c0)
         oracles.append(oracle.Oracle(M=M, ld=width, D=valid, dims=(), batch=0, seed=w.seed, P=P, X0=x0, col0=c0,
                                      **hyper(w, rho)))
