@@ -157,8 +157,8 @@ def test_cfg5_full_shape_sampled_workers():
     T, last = oracle.thresholds(inp["P"])
     wtab = oracle.mix_weights(inp["P"], None, h["lr"], h["rho"])
     gpu.step(0)
-    peers = gpu.peers.cpu().numpy()
-    assert np.array_equal(peers, oracle.sample_peers(T, last, w.seed, 0))
+    peers = oracle.sample_peers(T, last, w.seed, 0)
+    assert np.array_equal(gpu.peers.cpu().numpy(), peers)
     idx = oracle.sample_batch(w.M, w.batch, inp["shard_off"], w.seed, 0)
     G, X1 = gpu.get("g").cpu().numpy(), gpu.get("x").cpu().numpy()
     for i in (0, 37, 127):
