@@ -25,6 +25,14 @@ def test_activity_by_hand_and_uniform(ora):
     t2 = np.full((5, 5), 3.0)
     P2 = np.full((5, 5), 0.25) - 0.25 * np.eye(5)
     assert np.allclose(ora.activity(t2, P2), 0.2)
+    # a worker that sometimes selects itself: d_ii = 0 in Eq. (d3), so p_ii t_ii adds nothing.
+    # tbar = (0.5 * 1 + 0.25 * 2, 2.2, 3.4) = (1.0, 2.2, 3.4) whatever t_00 is
+    t3 = t.copy()
+    t3[0, 0] = 7.0
+    P3 = P.copy()
+    P3[0] = [.25, .5, .25]
+    f = np.array([1 / 1.0, 1 / 2.2, 1 / 3.4])
+    assert np.allclose(ora.activity(t3, P3), f / f.sum(), rtol=1e-14)
     # a missing edge removes that term from the mean iteration time
     adj = np.ones((3, 3), np.uint8) - np.eye(3, dtype=np.uint8)
     adj[0, 2] = 0

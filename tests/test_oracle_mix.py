@@ -224,3 +224,30 @@ def test_fixed_weight_one_half_is_plain_averaging(ora):
     P3 /= P3.sum(1, keepdims=True)
     w3 = ora.mix_weights_fixed(P3, 0.3)
     assert w3[0, 2] == 0 and np.all(np.diag(w3) == 0) and set(np.unique(w3)) == {0.0, 0.3}
+
+
+def test_iteration_sequencing_of_the_oracle_class(ora):
+    """oracle.Oracle chains the functions pinned above; two closed forms pin the chaining itself.
+    (a) Every worker selects itself (p_ii = 1: local step only), plain SGD: after iteration `it` the state is
+    x - alpha g(it) with the synthetic gradient OF THAT ITERATION (Algorithm 2: gradient first, then the update).
+    (b) Two workers that always select each other, no gradient: the new copies become the current ones, so
+    x_1 - x_2 shrinks by (1 - 2 alpha rho) per iteration."""
+    rng = np.random.default_rng(12)
+    ld, alpha, sigma = 64, 0.1, 0.05
+    X0 = rng.standard_normal((3, ld)).astype(np.float32)
+    o = ora.Oracle(M=3, ld=ld, D=ld, dims=(), batch=0, lr=alpha, momentum=0.0, weight_decay=0.0, rho=0.2, grad_sigma=sigma,
+                   seed=21, P=np.eye(3), X0=X0)
+    want = X0.astype(np.float64)
+    for it in range(3):
+        assert list(o.step(it)) == [0, 1, 2]
+        g = ora.synth_grad(3, ld, ld, sigma, 21, it)
+        assert np.abs(g).max() > 0
+        want = (want - alpha * g.astype(np.float64)).astype(np.float32).astype(np.float64)
+        np.testing.assert_allclose(o.X, want, rtol=0, atol=1e-7)
+    rho, T = 1.5, 6
+    Y0 = rng.standard_normal((2, ld)).astype(np.float32)
+    o2 = ora.Oracle(M=2, ld=ld, D=ld, dims=(), batch=0, lr=alpha, momentum=0.0, weight_decay=0.0, rho=rho, grad_sigma=0.0,
+                    seed=5, P=np.array([[0.0, 1.0], [1.0, 0.0]]), X0=Y0)
+    for it in range(T):
+        o2.step(it)
+    np.testing.assert_allclose(o2.X[0] - o2.X[1], (1 - 2 * alpha * rho) ** T * (Y0[0].astype(np.float64) - Y0[1]), rtol=0, atol=1e-6)

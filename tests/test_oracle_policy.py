@@ -146,6 +146,14 @@ def test_mix_weight_table(ora):
     w_full = ora.mix_weights(P, None, alpha, rho)
     off = (P > 0) & ~np.eye(M, dtype=bool)
     np.testing.assert_allclose(w_full[off], alpha * rho / P[off], rtol=1e-14)
+    # a one-way edge: d_01 = 1, d_10 = 0 (the connection matrix need not be symmetric), numbers by hand:
+    # w_01 = 0.1 * 0.3 * (1 + 0) / (2 * 0.25) = 0.06, w_02 = 0.1 * 0.3 * 2 / (2 * 0.75) = 0.04,
+    # w_10 = 0.1 * 0.3 * (0 + 1) / (2 * 0.5) = 0.03 (p_10 > 0 although d_10 = 0: the weight only reads d)
+    adj3 = np.array([[0, 1, 1], [0, 0, 1], [1, 1, 0]], np.uint8)
+    P3 = np.array([[0, .25, .75], [.5, 0, .5], [.5, .5, 0]])
+    w3 = ora.mix_weights(P3, adj3, alpha, rho)
+    assert w3[0, 1] == pytest.approx(0.06, rel=1e-14) and w3[0, 2] == pytest.approx(0.04, rel=1e-14)
+    assert w3[1, 0] == pytest.approx(0.03, rel=1e-14)
 
 
 @pytest.mark.parametrize("name", WORKLOAD_NAMES)

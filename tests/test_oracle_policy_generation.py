@@ -23,6 +23,22 @@ def _ring_adj(M, extra=()):
     return a
 
 
+def test_lower_bounds_are_constraint_o3_and_activity_is_eq_d4():
+    """(o3): p_im >= alpha rho (d_im + d_mi) on the edges of worker i, by hand on a graph with a one-way edge;
+    Eq. (d3)/(d4): tbar = (1.5, 2.2, 3.4) for the times and policy below, p_i proportional to 1 / tbar_i, so the
+    fastest worker is active most often."""
+    d = np.array([[0, 1, 1], [0, 0, 1], [1, 1, 0]], float)           # d_01 = 1, d_10 = 0
+    lb = pol.lower_bounds(d, 0.1, 0.5)
+    want = np.array([[0, 0.05, 0.10], [0, 0, 0.10], [0.10, 0.10, 0]])  # 0.1 * 0.5 * (d_im + d_mi) where d_im = 1
+    np.testing.assert_allclose(lb, want, rtol=1e-14)
+    t = np.array([[0, 1, 2.0], [1, 0, 4], [2, 4, 0]])
+    P = np.array([[0, .5, .5], [.6, 0, .4], [.3, .7, 0]])
+    f = np.array([1 / 1.5, 1 / 2.2, 1 / 3.4])
+    p_act = pol.worker_activity(t, pol.adjacency(3), P)
+    np.testing.assert_allclose(p_act, f / f.sum(), rtol=1e-14)
+    assert p_act[0] > p_act[1] > p_act[2]
+
+
 @pytest.mark.parametrize("recipe,M,adj,rf", [("two_tier_10", 8, None, 0.3), ("lognormal_1p5", 12, None, 0.1),
                                              ("three_tier_100_10_1", 16, None, 0.3), ("two_tier_10", 6, "ring", 0.1)])
 def test_row_solution_is_optimal_for_the_linear_program_and_feasible(recipe, M, adj, rf):
