@@ -8,6 +8,8 @@
 #include "kernels.h"
 #include "layout.h"
 
+#include <type_traits>
+
 namespace netmax {
 
 constexpr int TM = 64, TN = 64, TK = 32, GEMM_THREADS = 256;
@@ -19,15 +21,20 @@ constexpr int MAX_BATCH = 1024;
 enum : int { IN_GATHER_F32 = 0, IN_GATHER_BF16 = 1, IN_ACT_F32 = 2, IN_ACT_BF16 = 3 };
 
 __device__ __forceinline__ float as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
-// round != 0: the operand rounded to bfloat16; both candidates are computed, no branch
-__device__ __forceinline__ float maybe_round(float x, int round) { const float r = round_bf16(x); return round ? r : x; }
+// Operands are rounded to bfloat16 exactly when the layer inputs are stored as bfloat16 (the odd kinds): a property
+// of the instantiation, so the fp32 kernels carry no rounding code.
+template <int KIND> __device__ __forceinline__ float operand(float x)
+{
+    if constexpr ((KIND & 1) != 0) return round_bf16(x);
+    else return x;
+}
 
 // Input of layer l for worker g, batch row r, feature k.  bits<KIND>() is one unconditional load (the caller
 // passes coordinates inside the operand), value<KIND>() turns what was loaded into the multiplicand.
 struct LayerInput {
     const void *feats; const int64_t *row0; const int32_t *idx; const float *act_prev;
     const uint16_t *act_prev_bf16;
-    int B; int64_t din; int kind; int round;
+    int B; int64_t din; int kind;
     // rows: the worker's batch as absolute data rows (row0[g] + idx[g][b]), staged in LDS by the kernel
     template <int KIND> __device__ __forceinline__ uint32_t bits(int g, int r, int64_t k, const int64_t *rows) const
     {
@@ -39,7 +46,7 @@ struct LayerInput {
     template <int KIND> __device__ __forceinline__ float value(uint32_t u) const
     {
         if constexpr (KIND == IN_GATHER_BF16 || KIND == IN_ACT_BF16) return as_float(u << 16);
-        else return maybe_round(as_float(u), round);
+        else return as_float(u);
     }
     // the same element as bits(): element index of feature 0 of batch row r, and the load of index + k
     template <int KIND> __device__ __forceinline__ int64_t row_index(int g, int r, const int64_t *rows) const
@@ -66,7 +73,7 @@ __device__ __forceinline__ size_t tiled_offset_quick(int M, int i, int64_t j)
 // Z = A W + b, optional ReLU.  rows = batch, cols = dout, K = din.
 struct FwdProblem {
     static constexpr bool A_K_FAST = true, B_C_FAST = true;
-    LayerInput in; const float *X; int64_t woff, din, dout; int M, B, relu, round; float *out;
+    LayerInput in; const float *X; int64_t woff, din, dout; int M, B, relu; float *out;
     uint16_t *out_bf16, *out_bf16_t;     // optional bfloat16 copies: [B][dout] and transposed [dout][B]
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return dout; }
@@ -81,7 +88,7 @@ struct FwdProblem {
     {
         return ((const uint32_t *)X)[tiled_offset(M, g, woff + k * dout + c)];
     }
-    __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    template <int AK> __device__ float b_val(uint32_t u) const { return operand<AK>(as_float(u)); }
     // the operands as base + k * step: what does not depend on the contraction index is computed once per thread
     static constexpr bool A_AFFINE = true;
     template <int AK> __device__ int64_t a_base(int g, int64_t r, const int64_t *rows) const { return in.row_index<AK>(g, (int)r, rows); }
@@ -107,7 +114,7 @@ struct FwdProblem {
 struct DgradProblem {
     static constexpr bool A_K_FAST = true, B_C_FAST = false;
     const float *dz; const float *X; const float *act; const uint16_t *act_bf16; int64_t woff, din, dout;
-    int M, B, round; float *out; uint16_t *out_bf16, *out_bf16_t;
+    int M, B; float *out; uint16_t *out_bf16, *out_bf16_t;
     __device__ int rows() const { return B; }
     __device__ int64_t cols() const { return din; }
     __device__ int64_t depth() const { return dout; }
@@ -116,12 +123,12 @@ struct DgradProblem {
     {
         return ((const uint32_t *)dz)[((size_t)g * B + r) * dout + k];
     }
-    template <int AK> __device__ float a_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    template <int AK> __device__ float a_val(uint32_t u) const { return operand<AK>(as_float(u)); }
     __device__ uint32_t b_bits(int g, int64_t k, int64_t c) const
     {
         return ((const uint32_t *)X)[tiled_offset(M, g, woff + c * dout + k)];
     }
-    __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    template <int AK> __device__ float b_val(uint32_t u) const { return operand<AK>(as_float(u)); }
     static constexpr bool A_AFFINE = true;
     template <int AK> __device__ int64_t a_base(int g, int64_t r, const int64_t *) const { return ((int64_t)g * B + r) * dout; }
     __device__ int64_t a_step() const { return 1; }
@@ -146,7 +153,7 @@ struct DgradProblem {
 // dW = A^T dZ.  rows = din, cols = dout, K = batch.
 struct WgradProblem {
     static constexpr bool A_K_FAST = false, B_C_FAST = true;
-    LayerInput in; const float *dz; int64_t woff, din, dout; int M, B, round; float *G;
+    LayerInput in; const float *dz; int64_t woff, din, dout; int M, B; float *G;
     __device__ int64_t rows() const { return din; }
     __device__ int64_t cols() const { return dout; }
     __device__ int64_t depth() const { return B; }
@@ -160,7 +167,7 @@ struct WgradProblem {
     {
         return ((const uint32_t *)dz)[((size_t)g * B + k) * dout + c];
     }
-    __device__ float b_val(uint32_t u) const { return maybe_round(as_float(u), round); }
+    template <int AK> __device__ float b_val(uint32_t u) const { return operand<AK>(as_float(u)); }
     static constexpr bool A_AFFINE = false;      // the batch row of contraction index k is looked up (gathered data)
     template <int AK> __device__ int64_t a_base(int, int64_t, const int64_t *) const { return 0; }
     __device__ int64_t a_step() const { return 0; }
@@ -200,37 +207,41 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
     constexpr int A_PER = (TM * TK) / GEMM_THREADS, B_PER = (TN * TK) / GEMM_THREADS;
     uint32_t ra[A_PER], rb[B_PER];
     unsigned a_ok = 0, b_ok = 0;          // bit q: element q of the fetch lies inside the operand
-    // per element of a fetch: its index at contraction index 0 (row / column clamped into the operand)
-    int64_t a_idx0[A_PER], b_idx0[B_PER];
+    // per element of a fetch: its index at contraction index kk (its own offset inside a step; row / column clamped
+    // into the operand), so that a step only adds k0 * step, the same number for the whole workgroup
+    int64_t a_idx[A_PER], b_idx[B_PER];
     unsigned a_in = 0, b_in = 0;          // bit q: the row / column of element q exists
+    const int64_t a_step = p.a_step(), b_step = p.b_step();
 #pragma unroll
     for (int q = 0; q < A_PER; ++q) {
         const int e = tid + q * GEMM_THREADS;
-        const int r = Problem::A_K_FAST ? e / TK : e % TM;
+        const int r = Problem::A_K_FAST ? e / TK : e % TM, kk = Problem::A_K_FAST ? e % TK : e / TM;
         const int64_t rr = row0 + r;
         a_in |= (unsigned)(rr < R) << q;
-        a_idx0[q] = Problem::A_AFFINE ? p.template a_base<AK>(g, rr < R ? rr : R - 1, s_rows) : 0;
+        a_idx[q] = Problem::A_AFFINE ? p.template a_base<AK>(g, rr < R ? rr : R - 1, s_rows) + kk * a_step : 0;
     }
 #pragma unroll
     for (int q = 0; q < B_PER; ++q) {
         const int e = tid + q * GEMM_THREADS;
-        const int c = Problem::B_C_FAST ? e % TN : e / TK;
+        const int c = Problem::B_C_FAST ? e % TN : e / TK, kk = Problem::B_C_FAST ? e / TN : e % TK;
         const int64_t cc = col0 + c;
         b_in |= (unsigned)(cc < C) << q;
-        b_idx0[q] = p.b_base(g, cc < C ? cc : C - 1);
+        b_idx[q] = p.b_base(g, cc < C ? cc : C - 1) + kk * b_step;
     }
-    const int64_t a_step = p.a_step(), b_step = p.b_step();
-    auto fetch = [&](int64_t k0) {
-        a_ok = b_ok = 0;
+    // full = std::true_type: every contraction index of the step is below K, nothing to clamp or mask along K
+    auto fetch = [&](int64_t k0, auto full) {
+        constexpr bool FULL = decltype(full)::value;
+        a_ok = FULL ? a_in : 0u;
+        b_ok = FULL ? b_in : 0u;
+        const int64_t a_k0 = k0 * a_step, b_k0 = k0 * b_step;
 #pragma unroll
         for (int q = 0; q < A_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
-            int kk, r;
-            if (Problem::A_K_FAST) { kk = e % TK; r = e / TK; } else { r = e % TM; kk = e / TM; }
-            const int64_t kq = k0 + kk, kc = kq < K ? kq : K - 1;
-            a_ok |= (unsigned)(((a_in >> q) & 1u) && kq < K) << q;
+            const int r = Problem::A_K_FAST ? e / TK : e % TM, kk = Problem::A_K_FAST ? e % TK : e / TM;
+            const int64_t kq = k0 + kk, kc = (FULL || kq < K) ? kq : K - 1;
+            if (!FULL) a_ok |= (unsigned)(((a_in >> q) & 1u) && kq < K) << q;
             if constexpr (Problem::A_AFFINE) {
-                ra[q] = p.template a_at<AK>(a_idx0[q] + kc * a_step);
+                ra[q] = p.template a_at<AK>(FULL ? a_idx[q] + a_k0 : a_idx[q] + (kc - kk) * a_step);
             } else {
                 const int64_t rr = row0 + r;
                 ra[q] = p.template a_bits<AK>(g, rr < R ? rr : R - 1, kc, s_rows);
@@ -240,15 +251,19 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
         for (int q = 0; q < B_PER; ++q) {
             const int e = tid + q * GEMM_THREADS;
             const int kk = Problem::B_C_FAST ? e / TN : e % TK;
-            const int64_t kq = k0 + kk, kc = kq < K ? kq : K - 1;
-            b_ok |= (unsigned)(((b_in >> q) & 1u) && kq < K) << q;
-            rb[q] = p.b_at(g, b_idx0[q] + kc * b_step);
+            const int64_t kq = k0 + kk, kc = (FULL || kq < K) ? kq : K - 1;
+            if (!FULL) b_ok |= (unsigned)(((b_in >> q) & 1u) && kq < K) << q;
+            rb[q] = p.b_at(g, FULL ? b_idx[q] + b_k0 : b_idx[q] + (kc - kk) * b_step);
         }
+    };
+    auto fetch_step = [&](int64_t k0) {
+        if (k0 + TK <= K) fetch(k0, std::true_type{});
+        else fetch(k0, std::false_type{});
     };
     gemm_acc acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    fetch(0);
+    fetch_step(0);
     for (int64_t k0 = 0; k0 < K; k0 += TK) {
         __syncthreads();                       // the previous step's reads of LDS are done
 #pragma unroll
@@ -264,11 +279,11 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
             const int e = tid + q * GEMM_THREADS;
             int kk, c;
             if (Problem::B_C_FAST) { c = e % TN; kk = e / TN; } else { kk = e % TK; c = e / TK; }
-            const float v = p.b_val(rb[q]);
+            const float v = p.template b_val<AK>(rb[q]);
             Bs[kk][c] = ((b_ok >> q) & 1u) ? v : 0.0f;
         }
         __syncthreads();
-        if (k0 + TK < K) fetch(k0 + TK);
+        if (k0 + TK < K) fetch_step(k0 + TK);
 #pragma unroll
         for (int kk = 0; kk < TK; kk += 2) {
             const int k = kk + (lane >> 5);
@@ -288,10 +303,11 @@ template <class Problem> static dim3 gemm_grid(int groups, int64_t rows, int64_t
     return dim3((unsigned)((cols + TN - 1) / TN), (unsigned)((rows + TM - 1) / TM), (unsigned)groups);
 }
 
-static void launch_gemm(hipStream_t s, const DgradProblem &p, int groups, int64_t rows, int64_t cols)
+static void launch_gemm(hipStream_t s, const DgradProblem &p, int kind, int groups, int64_t rows, int64_t cols)
 {
-    hipLaunchKernelGGL((grouped_gemm_kernel<DgradProblem, IN_ACT_F32>), gemm_grid<DgradProblem>(groups, rows, cols),
-                       dim3(GEMM_THREADS), 0, s, p);
+    const dim3 grid = gemm_grid<DgradProblem>(groups, rows, cols);
+    if (kind == IN_ACT_BF16) hipLaunchKernelGGL((grouped_gemm_kernel<DgradProblem, IN_ACT_BF16>), grid, dim3(GEMM_THREADS), 0, s, p);
+    else hipLaunchKernelGGL((grouped_gemm_kernel<DgradProblem, IN_ACT_F32>), grid, dim3(GEMM_THREADS), 0, s, p);
 }
 
 template <class Problem>
@@ -402,7 +418,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
         in.feats = p.feats; in.row0 = p.row0; in.idx = p.idx;
         in.act_prev = (l > 0 && !bf) ? p.act[l] : nullptr;
         in.act_prev_bf16 = (l > 0 && bf) ? p.hb[l] : nullptr;
-        in.B = p.B; in.din = p.dims[l]; in.round = p.bf16;
+        in.B = p.B; in.din = p.dims[l];
         in.kind = l == 0 ? (bf ? IN_GATHER_BF16 : IN_GATHER_F32) : (bf ? IN_ACT_BF16 : IN_ACT_F32);
         return in;
     };
@@ -420,7 +436,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
         }
         FwdProblem f;
         f.in = input_of(l); f.X = X; f.M = p.M; f.woff = p.woff[l]; f.din = p.dims[l]; f.dout = p.dims[l + 1];
-        f.B = p.B; f.relu = !last; f.round = p.bf16;
+        f.B = p.B; f.relu = !last;
         f.out = (last || !bf) ? p.act[l + 1] : nullptr;
         f.out_bf16 = (bf && !last) ? p.hb[l + 1] : nullptr;
         f.out_bf16_t = (bf && !last) ? p.ht[l + 1] : nullptr;
@@ -446,7 +462,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
         } else {
             WgradProblem wg;
             wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
-            wg.B = p.B; wg.round = p.bf16; wg.G = G;
+            wg.B = p.B; wg.G = G;
             launch_gemm(s, wg, wg.in.kind, p.M, din, dout);
         }
         if (!bias_done[l]) {
@@ -463,11 +479,11 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
             } else {
                 DgradProblem dg;
                 dg.dz = p.dz[cur]; dg.X = X; dg.act = bf ? nullptr : p.act[l]; dg.act_bf16 = bf ? p.hb[l] : nullptr;
-                dg.M = p.M; dg.woff = p.woff[l]; dg.din = din; dg.dout = dout; dg.B = p.B; dg.round = p.bf16;
+                dg.M = p.M; dg.woff = p.woff[l]; dg.din = din; dg.dout = dout; dg.B = p.B;
                 dg.out = p.dz[cur ^ 1];
                 dg.out_bf16 = bf ? p.dzb[cur ^ 1] : nullptr;
                 dg.out_bf16_t = bf ? p.dzt[cur ^ 1] : nullptr;
-                launch_gemm(s, dg, p.M, p.B, din);
+                launch_gemm(s, dg, bf ? IN_ACT_BF16 : IN_ACT_F32, p.M, p.B, din);     // the kind only says whether operands are rounded
             }
             cur ^= 1;
         }
