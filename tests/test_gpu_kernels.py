@@ -271,3 +271,45 @@ def test_degenerate_perceptron_shapes(ora, over):
             assert rel_err_rows(G, o.G) < 1e-5
     assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < 1e-5
     gpu.close()
+
+
+def _random_case(seed):
+    """A small seeded configuration: (base workload, overrides, bf16?)."""
+    rng = np.random.default_rng(1000 + seed)
+    kind = seed % 4
+    M = int(rng.integers(2, 10))
+    if kind == 0:
+        return "cfg3" if seed % 8 == 0 else "cfg4", dict(M=M, D=int(rng.integers(1, 6000))), False
+    n_layers = int(rng.integers(1, 4))
+    if kind == 3 and seed % 8 == 3:        # shapes of the matrix-core kernels: widths multiple of 128, 32 | batch <= 128
+        dims = tuple(int(128 * rng.integers(1, 3)) for _ in range(max(2, n_layers))) + (int(rng.integers(2, 13)),)
+        batch = int(32 * rng.integers(1, 5))
+    else:
+        dims = tuple(int(rng.integers(1, 71)) for _ in range(n_layers)) + (int(rng.integers(2, 13)),)
+        batch = int(rng.integers(1, 41))
+    over = dict(M=M, dims=dims, batch=batch, n_per_worker=int(batch + rng.integers(0, 60)))
+    return ("cfg1", over, False) if kind == 1 else (("cfg2", over, False) if kind == 2 else ("cfg5", over, True))
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_small_configurations(ora, seed):
+    """Seeded random shapes (worker counts, widths, depths, batch and shard sizes that are multiples of nothing)
+    through all entry points of an iteration, three iterations each, against the oracle."""
+    name, over, bf16 = _random_case(seed)
+    w = workload(name, **over)
+    inp = inputs_of(w)
+    if w.model != "flat":
+        inp["labels"] = np.minimum(inp["labels"], w.dims[-1] - 1).astype(np.int32)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp, operands_bf16=bf16)
+    for it in range(3):
+        gpu.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it)), (name, over)
+        if it == 0:                                       # from identical state: the gradient itself
+            G = gpu.get("g").cpu().numpy()
+            assert np.all(G[:, w.D:] == 0)
+            scale = max(float(np.abs(o.G).max()), 1e-30)
+            assert float(np.abs(G - o.G).max()) <= (2e-3 if bf16 else 1e-5) * scale, (name, over)
+    err = rel_err_rows(gpu.get("x").cpu().numpy(), o.X)
+    assert err < (2e-3 if bf16 else 3e-5), (name, over, err)
+    assert gpu.consensus_dist() == pytest.approx(o.consensus_dist(), rel=1e-3 if bf16 else 1e-5, abs=1e-12)
+    gpu.close()
