@@ -665,3 +665,52 @@ def test_fused_update_with_weight_decay_fixed_weight_and_policy_change():
             assert np.array_equal(plain.get("x").cpu().numpy(), fused.get("x").cpu().numpy()), stage
             assert np.array_equal(plain.get("v").cpu().numpy(), fused.get("v").cpu().numpy()), stage
         plain.close(), fused.close()
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_small_configurations_run_modes(seed):
+    """The seeded random shapes of test_gpu_kernels through the other ways of running: netmax_run eagerly and as a
+    replayed graph (bit-identical to the separate calls), the flat models' fused variant (bit-identical), then the
+    asynchronous schedule from the state reached, against the oracle."""
+    import paper_2009_05766_amd as nm
+    from test_gpu_kernels import _random_case
+    from netmax_inputs import iteration_times
+    name, over, bf16 = _random_case(seed)
+    w = workload(name, **over)
+    inp = inputs_of(w)
+    if w.model != "flat":
+        inp["labels"] = np.minimum(inp["labels"], w.dims[-1] - 1).astype(np.int32)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        calls, eager, graph = make_gpu(w, inp), make_gpu(w, inp), make_gpu(w, inp)
+        o = make_oracle(w, inp, operands_bf16=bf16)
+        if w.model == "flat":
+            nm.netmax_set_fusion(eager.ctx, True)
+        for it in range(3):
+            calls.step(it)
+            assert np.array_equal(calls.peers.cpu().numpy(), o.step(it))
+        eager.run(0, 3)
+        graph.run(0, 2, use_graph=True)
+        graph.run(2, 1, use_graph=True)
+        side.synchronize()
+        for other in (eager, graph):
+            for what in ("x", "v"):
+                assert np.array_equal(calls.get(what).cpu().numpy(), other.get(what).cpu().numpy()), (name, over, what)
+        tol = 2e-3 if bf16 else 3e-5
+        assert rel_err_rows(calls.get("x").cpu().numpy(), o.X) < tol
+        # asynchronous schedule on top: the oracle's state goes to the GPU first, both then take the same global steps
+        _sync_gpu_from_oracle(calls, o)
+        t = iteration_times("two_tier_10", w.M)
+        p_act = nm.netmax_activity(t, inp["P"])
+        nm.netmax_set_activity(calls.ctx, p_act)
+        o.set_activity(p_act)
+        n = 5
+        active = torch.zeros(n, dtype=torch.int32, device="cuda")
+        peers = torch.zeros(n, dtype=torch.int32, device="cuda")
+        nm.netmax_async_run(calls.ctx, 3, n, active, peers)
+        side.synchronize()
+        want = np.array([o.async_step(3 + k) for k in range(n)], dtype=np.int32)
+        assert np.array_equal(active.cpu().numpy(), want[:, 0]) and np.array_equal(peers.cpu().numpy(), want[:, 1])
+        assert rel_err_rows(calls.get("x").cpu().numpy(), o.X) < tol
+        for g in (calls, eager, graph):
+            g.close()
