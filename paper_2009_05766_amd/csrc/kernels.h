@@ -45,6 +45,7 @@ void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float
                 const int32_t *peer, const float *w, float alpha, float mu, float wd);
 // Once per device before the first launch_mix: lets the kernel be launched with its large (unused) LDS request.
 hipError_t prepare_mix();
+hipError_t prepare_mix_synth();      // the same for launch_mix_synth
 
 // Flat models: the synthetic gradient generated inside the update (g is still written).
 void launch_mix_synth(hipStream_t s, int M, int64_t D, int64_t ld, const float *Xcur, float *G, float *V, float *Xnext,

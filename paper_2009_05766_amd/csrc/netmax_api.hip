@@ -295,6 +295,7 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
 
     INIT_TRY(hipGetDevice(&ctx->device));
     INIT_TRY(prepare_mix());
+    INIT_TRY(prepare_mix_synth());
     INIT_TRY(hipMalloc(&ctx->d_thr, mm * sizeof(uint32_t)));
     INIT_TRY(hipMalloc(&ctx->d_last, M * sizeof(int32_t)));
     INIT_TRY(hipMalloc(&ctx->d_w, mm * sizeof(float)));
