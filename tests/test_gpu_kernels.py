@@ -96,7 +96,10 @@ def test_synthetic_gradient(ora, M, D):
 
 
 @pytest.mark.parametrize("M,D,mu,wd", [(8, 2048 * 3 + 64 * 5, 0.9, 0.0), (5, 100, 0.0, 0.0), (16, 33000, 0.9, 1e-4),
-                                        (2, 4096, 0.5, 0.0), (64, 2048 * 17, 0.9, 0.0)])
+                                        (2, 4096, 0.5, 0.0), (64, 2048 * 17, 0.9, 0.0),
+                                        # enough slots for the large-problem form of the kernel (four slots per
+                                        # workgroup): worker counts that are no multiple of 4, tile counts no multiple of 8
+                                        (7, 2048 * 2400 - 5, 0.9, 0.0), (130, 2048 * 131 + 3, 0.9, 1e-4)])
 def test_mix_one_step(ora, M, D, mu, wd):
     w = workload("cfg3", M=M, D=D)
     inp = inputs_of(w)
