@@ -12,7 +12,7 @@
 // them together and only then stores: the memory controllers see bursts of reads and bursts of writes of a few
 // streams instead of many interleaved ones.  Measured on M = 64 x 11.2 M parameters: 78 to 79 % of the HBM peak,
 // against 73 % for one slot per workgroup with as many workgroups resident as fit (77 % with two resident).
-// Small problems (a few slots per compute unit) keep the one-slot form: there the tail matters, not the rate.
+// Small problems (a few slots per compute unit) and small worker counts keep the one-slot form.
 #include "kernels.h"
 #include "layout.h"
 #include "vec.h"
@@ -26,6 +26,7 @@ static_assert(MIX_VECS * 4 * MIX_LANES == TILE, "256 threads cover exactly one t
 // the large form asks for a whole compute unit's LDS (never touched): one resident workgroup per compute unit
 constexpr unsigned MIX_LDS_BYTES = 160 * 1024 - 512;
 constexpr int64_t MIX_SMALL_SLOTS = 16384;         // below this many slots: the one-slot form
+constexpr int MIX_SMALL_M = 32;                    // and below this many workers (measured: 5 % slower there at M = 8, 16)
 
 template <int SLOTS, int GROUPS, bool GATHERED>
 __global__ void __launch_bounds__(MIX_LANES * GROUPS)
@@ -91,7 +92,7 @@ void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float
 {
     const int64_t n_tiles = ld / TILE;
     const int64_t slots_per_xcd = (n_tiles + N_XCD - 1) / N_XCD * M;
-    if (n_tiles * M < MIX_SMALL_SLOTS) {
+    if (n_tiles * M < MIX_SMALL_SLOTS || M < MIX_SMALL_M) {
         hipLaunchKernelGGL((mix_kernel<1, 1, false>), dim3((unsigned)(slots_per_xcd * N_XCD)), dim3(MIX_LANES), 0, s, M,
                            n_tiles, Xcur, G, V, Xnext, peer, w, alpha, mu, wd);
     } else {
