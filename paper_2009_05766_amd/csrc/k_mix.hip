@@ -40,7 +40,7 @@ mix_kernel(int M, int64_t n_tiles, const float *__restrict__ Xcur, const float *
     const unsigned slot0 = ((bid / N_XCD) * GROUPS + group) * SLOTS;
 
     f32x4 rx[SLOTS][MIX_VECS], rp[SLOTS][MIX_VECS], rv[SLOTS][MIX_VECS], rg[SLOTS][MIX_VECS];
-    size_t own[SLOTS];
+    size_t own[SLOTS], other[SLOTS];
     float wi[SLOTS];
     bool live[SLOTS];
 #pragma unroll
@@ -48,43 +48,60 @@ mix_kernel(int M, int64_t n_tiles, const float *__restrict__ Xcur, const float *
         const unsigned slot = slot0 + s, tile_in_xcd = slot / (unsigned)M, i = slot - tile_in_xcd * (unsigned)M;
         const int64_t tile = (int64_t)tile_in_xcd * N_XCD + xcd;
         live[s] = tile < n_tiles;
-        if (live[s]) {
-            int m = peer[i];
-            if ((unsigned)m >= (unsigned)M) m = (int)i;   // an index outside [0, M) is treated as a self draw
-            wi[s] = w[(size_t)i * M + m];
-            own[s] = ((size_t)tile * M + i) * TILE;
-            const float *x = Xcur + own[s], *xp = Xcur + ((size_t)tile * M + m) * TILE, *g = G + own[s];
-            const float *v = V + own[s];
-#pragma unroll
-            for (int u = 0; u < MIX_VECS; ++u) {
-                const int j = (u * MIX_LANES + lane) * 4;
-                rx[s][u] = load4(x + j);            // kept cacheable: another worker of this tile may pull this row
-                rp[s][u] = load4(xp + j);
-                rv[s][u] = load4_stream(v + j);
-                rg[s][u] = load4_stream(g + j);
-            }
-        }
+        int m = live[s] ? peer[i] : 0;
+        if ((unsigned)m >= (unsigned)M) m = (int)i;       // an index outside [0, M) is treated as a self draw
+        wi[s] = live[s] ? w[(size_t)i * M + m] : 0.0f;
+        own[s] = live[s] ? ((size_t)tile * M + i) * TILE : 0;
+        other[s] = live[s] ? ((size_t)tile * M + m) * TILE : 0;
     }
+    // Requests go out matrix by matrix over all slots of the group (x, v, g, then the peers' rows), not slot by
+    // slot: measured 1.5 points of the HBM peak better with several slots per group.
+    const int j0 = (int)lane * 4;
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s)
+        if (live[s])
+#pragma unroll
+            for (int u = 0; u < MIX_VECS; ++u)
+                rx[s][u] = load4(Xcur + own[s] + u * MIX_LANES * 4 + j0);    // kept cacheable: another worker of this tile may pull this row
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s)
+        if (live[s])
+#pragma unroll
+            for (int u = 0; u < MIX_VECS; ++u) rv[s][u] = load4_stream(V + own[s] + u * MIX_LANES * 4 + j0);
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s)
+        if (live[s])
+#pragma unroll
+            for (int u = 0; u < MIX_VECS; ++u) rg[s][u] = load4_stream(G + own[s] + u * MIX_LANES * 4 + j0);
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s)
+        if (live[s])
+#pragma unroll
+            for (int u = 0; u < MIX_VECS; ++u) rp[s][u] = load4(Xcur + other[s] + u * MIX_LANES * 4 + j0);
     if (GATHERED) {
         // every load of the workgroup has arrived before its first store leaves
         __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0), the other counters untouched
         __syncthreads();
     }
+    f32x4 xo[SLOTS][MIX_VECS], vo[SLOTS][MIX_VECS];
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s) {
-        if (live[s]) {
-            float *v = V + own[s], *xn = Xnext + own[s];
+    for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
-            for (int u = 0; u < MIX_VECS; ++u) {
-                const int j = (u * MIX_LANES + lane) * 4;
-                const f32x4 vn = mu * rv[s][u] + rg[s][u] + wd * rx[s][u];   // v' = mu v + g + wd x
-                const f32x4 h = rx[s][u] - alpha * vn;                       // first-step update
-                const f32x4 out = h - wi[s] * (h - rp[s][u]);                // second-step update towards the peer
-                store4_stream(xn + j, out);
-                store4_stream(v + j, vn);
-            }
+        for (int u = 0; u < MIX_VECS; ++u) {
+            vo[s][u] = mu * rv[s][u] + rg[s][u] + wd * rx[s][u];             // v' = mu v + g + wd x
+            const f32x4 h = rx[s][u] - alpha * vo[s][u];                     // first-step update
+            xo[s][u] = h - wi[s] * (h - rp[s][u]);                           // second-step update towards the peer
         }
-    }
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s)
+        if (live[s])
+#pragma unroll
+            for (int u = 0; u < MIX_VECS; ++u) store4_stream(Xnext + own[s] + u * MIX_LANES * 4 + j0, xo[s][u]);
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s)
+        if (live[s])
+#pragma unroll
+            for (int u = 0; u < MIX_VECS; ++u) store4_stream(V + own[s] + u * MIX_LANES * 4 + j0, vo[s][u]);
 }
 
 void launch_mix(hipStream_t s, int M, int64_t ld, const float *Xcur, const float *G, float *V, float *Xnext,
