@@ -17,7 +17,8 @@ __global__ void __launch_bounds__(256) synth_grad_kernel(int M, int64_t D, int64
     const int q = (int)(blockIdx.x & 1) * 256 + (int)threadIdx.x;            // quad inside the tile
     for (int64_t tile = blockIdx.y; tile < n_tiles; tile += gridDim.y) {
         const int64_t j = tile * TILE + (int64_t)q * 4;                      // column of the first element
-        const f32x4 z = synth_grad4(seed, i, iter, j, D, sigma);
+        const f32x4 z = (tile + 1) * TILE <= D ? synth_grad4<true>(seed, i, iter, j, D, sigma)    // the same for the whole workgroup
+                                               : synth_grad4<false>(seed, i, iter, j, D, sigma);
         store4_stream(G + (((size_t)tile * M + i) << TILE_SHIFT) + q * 4, z);
     }
 }
