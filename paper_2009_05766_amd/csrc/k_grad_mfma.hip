@@ -447,6 +447,7 @@ constexpr int WG_PITCH = 128 + 8;            // bf16 elements per operand row in
 
 // STRIP: rows of W per workgroup (128 or 64), BN: columns per block step (128 or 64); waves 2 x 2, each
 // STRIP / 2 rows x BN / 2 columns.
+constexpr int WG_STAGE_PITCH = 132;                  // floats per row of the staged output block
 template <int STRIP, int BN>
 __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
 {
@@ -517,6 +518,27 @@ __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
 #pragma unroll
                 for (int j = 0; j < CJ; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
         }
+        if constexpr (STRIP == 64 && BN == 128) {
+            // The block goes through LDS (the space of the dZ^T block, which every wave has finished reading) and
+            // leaves as whole 512-byte row pieces, 16 bytes per lane, in one burst of stores per workgroup (measured:
+            // 15 us less per iteration of the 3072-1024-1024 perceptron than 4-byte stores straight from the accumulators).
+            float (*T)[WG_STAGE_PITCH] = reinterpret_cast<float (*)[WG_STAGE_PITCH]>(&Zt[0][0]);
+            static_assert(sizeof(float) * 64 * WG_STAGE_PITCH <= sizeof(uint16_t) * BN * WG_PITCH, "the staged block fits the operand block");
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < CJ; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) T[32 * wm + d_row(lane, v)][64 * wn + 32 * j + (lane & 31)] = acc[0][j][v];
+            __syncthreads();
+            const int cq = (t & 31) * 4, r_in = t >> 5;              // 32 lanes along the 128 columns, 8 rows per pass
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                const int row = pass * 8 + r_in;
+                const int64_t jj = p.woff + (r0 + row) * p.dout + (int64_t)nb * BN + cq;
+                __builtin_nontemporal_store(*reinterpret_cast<const f32x4_t *>(&T[row][cq]),
+                                            reinterpret_cast<f32x4_t *>(p.G + tiled_offset_fast(p.M, g, jj)));
+            }
+        } else {
         // column index inside the parameter row = lane part (fixed) + a part that is the same for the whole wave
 #pragma unroll
         for (int i = 0; i < RI; ++i)
@@ -527,6 +549,7 @@ __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
                     const int64_t uni = (int64_t)(32 * i + (v & 3) + 8 * (v >> 2)) * p.dout + (int64_t)nb * BN + 32 * j;
                     __builtin_nontemporal_store(acc[i][j][v], p.G + tiled_offset_fast(p.M, g, lane_col + uni));
                 }
+        }
     }
 }
 
