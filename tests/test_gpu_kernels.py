@@ -174,6 +174,12 @@ GRAD_CASES = [
     ("cfg5", dict(M=3, batch=96, n_per_worker=200, dims=(384, 128))),            # softmax regression, bf16
     ("cfg5", dict(M=9, batch=96, n_per_worker=150, dims=(256, 256, 128, 10))),   # workers not a multiple of 8, batch 96
     ("cfg5", dict(M=3, batch=64, n_per_worker=100, dims=(200, 128, 128, 10))),   # general first layer under matrix-core layers
+    # few outputs behind a wide layer (the narrow forward kernel): every input kind, 16- and 32-column padding,
+    # contractions longer than one chunk, batch no multiple of 16
+    ("cfg1", dict(M=3, batch=21, n_per_worker=40, dims=(1100, 10))),
+    ("cfg2", dict(M=3, batch=37, n_per_worker=60, dims=(40, 600, 27))),
+    ("cfg5", dict(M=3, batch=19, n_per_worker=50, dims=(30, 450, 12))),
+    ("cfg5", dict(M=2, batch=20, n_per_worker=50, dims=(400, 5))),
 ]
 
 # Gradient tolerances, relative L2 per worker.  fp32 operands: fp32 accumulation over at most a few
