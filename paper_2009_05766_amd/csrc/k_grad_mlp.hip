@@ -304,13 +304,13 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
 // (thread q takes k = q, q + 16, ...).  The weights of a chunk of the contraction are a run of consecutive
 // parameters (rows of W are dout long), copied to LDS as they lie; all loads of a chunk are requested before the
 // first is used.  The 16 partial sums of a row are added in a fixed butterfly order.  Products and sums in fp32.
-constexpr int NARROW_ROWS = 16, NARROW_SPLIT = 16, NARROW_THREADS = NARROW_ROWS * NARROW_SPLIT, NARROW_WEIGHTS = 8192;
+constexpr int NARROW_ROWS = 16, NARROW_SPLIT = 16, NARROW_THREADS = NARROW_ROWS * NARROW_SPLIT, NARROW_WEIGHTS = 2048;
 template <int AK, int CP>       // CP: outputs padded to 16 or 32
 __global__ void __launch_bounds__(NARROW_THREADS) fwd_narrow_kernel(FwdProblem p)
 {
     constexpr int CHUNK = NARROW_WEIGHTS / CP;                 // contraction indices per chunk
     constexpr int PER = CHUNK / NARROW_SPLIT, W_PER = NARROW_WEIGHTS / NARROW_THREADS;
-    __shared__ float Wl[NARROW_WEIGHTS];
+    __shared__ float Wl[NARROW_WEIGHTS + CP];                   // CP more: the padded columns of the last row read on
     __shared__ int64_t s_row[NARROW_ROWS];
     const int g = blockIdx.y, tid = threadIdx.x, r = tid / NARROW_SPLIT, q = tid % NARROW_SPLIT;
     const int b = blockIdx.x * NARROW_ROWS + r;
@@ -322,32 +322,33 @@ __global__ void __launch_bounds__(NARROW_THREADS) fwd_narrow_kernel(FwdProblem p
         s_row[tid] = (AK == IN_GATHER_F32 || AK == IN_GATHER_BF16) ? (in.row0[g] + in.idx[(size_t)g * in.B + bq]) * in.din
                                                                    : ((int64_t)g * in.B + bq) * in.din;
     }
+    if (tid < CP) Wl[NARROW_WEIGHTS + tid] = 0.0f;
     __syncthreads();
     const int64_t a_row = s_row[r];
     float acc[CP];
 #pragma unroll
     for (int c = 0; c < CP; ++c) acc[c] = 0.0f;
+    // Chunks are small (8 loads of each kind per thread) and every loop over them is unrolled completely, so that the
+    // staged values stay in registers; clamped unconditional loads, no predicates.
     for (int64_t k0 = 0; k0 < p.din; k0 += CHUNK) {
         const int n = (int)(p.din - k0 < CHUNK ? p.din - k0 : CHUNK), n_w = n * C;
         uint32_t av[PER], wv[W_PER];
 #pragma unroll
         for (int u = 0; u < PER; ++u) {
             const int kk = q + u * NARROW_SPLIT;
-            av[u] = 0u;
-            if (kk < n) av[u] = p.in.template load_index<AK>(a_row + k0 + kk);
+            av[u] = p.in.template load_index<AK>(a_row + k0 + (kk < n ? kk : n - 1));
         }
         const int64_t w0 = p.woff + k0 * p.dout;               // first parameter of the chunk
 #pragma unroll
         for (int u = 0; u < W_PER; ++u) {
             const int e = tid + u * NARROW_THREADS;
-            wv[u] = 0u;
-            if (e < n_w) wv[u] = ((const uint32_t *)p.X)[tiled_offset_quick(p.M, g, w0 + e)];
+            wv[u] = ((const uint32_t *)p.X)[tiled_offset_quick(p.M, g, w0 + (e < n_w ? e : n_w - 1))];
         }
         __syncthreads();                                       // the previous chunk has been used
 #pragma unroll
         for (int u = 0; u < W_PER; ++u) {
             const int e = tid + u * NARROW_THREADS;
-            if (e < n_w) Wl[e] = p.template b_val<AK>(wv[u]);
+            Wl[e < n_w ? e : n_w - 1] = p.template b_val<AK>(wv[u]);     // clamped slots all hold the last weight
         }
         __syncthreads();
 #pragma unroll
@@ -355,9 +356,9 @@ __global__ void __launch_bounds__(NARROW_THREADS) fwd_narrow_kernel(FwdProblem p
             const int kk = q + u * NARROW_SPLIT;
             const float a = kk < n ? p.template a_val<AK>(av[u]) : 0.0f;
             const float *wk = Wl + (kk < n ? kk : 0) * C;
+            // columns from C on multiply whatever follows the row (finite numbers); those sums are never stored
 #pragma unroll
-            for (int c = 0; c < CP; ++c)
-                if (c < C) acc[c] = fmaf(a, wk[c], acc[c]);
+            for (int c = 0; c < CP; ++c) acc[c] = fmaf(a, wk[c], acc[c]);
         }
     }
     // the 16 partial sums of a row sit in 16 neighbouring lanes: butterfly over lane distances 8, 4, 2, 1
@@ -367,8 +368,12 @@ __global__ void __launch_bounds__(NARROW_THREADS) fwd_narrow_kernel(FwdProblem p
         for (int d = NARROW_SPLIT / 2; d > 0; d >>= 1) acc[c] += __shfl_xor(acc[c], d, 64);
     if (b < p.B) {
 #pragma unroll
-        for (int c = 0; c < CP; ++c)
-            if (c % NARROW_SPLIT == q && c < C) p.store(g, b, c, acc[c]);
+        for (int c0 = 0; c0 < CP; c0 += NARROW_SPLIT) {        // thread q stores columns q, q + 16
+            float v = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NARROW_SPLIT; ++c) v = (c == q) ? acc[c0 + c] : v;
+            if (c0 + q < C) p.store(g, b, c0 + q, v);
+        }
     }
 }
 
@@ -531,9 +536,8 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
         f.out = (last || !bf) ? p.act[l + 1] : nullptr;
         f.out_bf16 = (bf && !last) ? p.hb[l + 1] : nullptr;
         f.out_bf16_t = (bf && !last) ? p.ht[l + 1] : nullptr;
-        // few outputs and a long contraction: the tiled kernel takes about 5 + 1.3 us per 32 input columns there, the
-        // narrow one about 20 us whatever the width (measured at 256 and 512 columns)
-        if (f.dout <= 32 && f.din >= 384) launch_fwd_narrow(s, f, f.in.kind, p.M);
+        // few outputs: the tiled kernel would pad them to a 64-column tile on one workgroup per worker
+        if (f.dout <= 32) launch_fwd_narrow(s, f, f.in.kind, p.M);
         else launch_gemm(s, f, f.in.kind, p.M, p.B, f.dout);
     }
     // loss and dZ of the last layer
