@@ -12,7 +12,7 @@
 
 namespace netmax {
 
-constexpr int TM = 64, TN = 64, TK = 32, GEMM_THREADS = 256;
+constexpr int TK = 32, GEMM_THREADS = 256;
 typedef float gemm_acc __attribute__((ext_vector_type(16)));
 constexpr int MAX_BATCH = 1024;
 
@@ -181,7 +181,7 @@ struct WgradProblem {
     }
 };
 
-// 64 x 64 output tile per workgroup, one 32 x 32 quadrant per wave on v_mfma_f32_32x32x2_f32 (fp32 operands,
+// 64 x 64 output tile per workgroup (32 x 32 in the SMALL variant), one 32 x 32 quadrant per wave on v_mfma_f32_32x32x2_f32 (fp32 operands,
 // exact products, fp32 accumulation), K in steps of 32 through LDS.  Lane l of the instruction supplies
 // A[row l % 32][k = l / 32] and B[k = l / 32][col l % 32] and holds D[8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
 // in result register v.  The operands of the
@@ -189,16 +189,20 @@ struct WgradProblem {
 // unconditional loads: coordinates beyond the operand are clamped into it and the value is replaced by zero
 // afterwards, the operand's kind AK is a template parameter and the worker's batch rows are resolved once into
 // LDS, so that no load waits for a branch or for another load.
-template <class Problem, int AK>
+template <class Problem, int AK, bool SMALL = false>
 __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
 {
+    // SMALL: a 32 x 32 output tile; the four waves split every step's contraction indices between them (wave w takes
+    // k = 8 w .. 8 w + 7) and their partial tiles are added through LDS at the end, in the order of the waves.  Four
+    // times as many workgroups with a quarter of the matrix instructions per step each: for few, long problems.
+    constexpr int TM = SMALL ? 32 : 64, TN = SMALL ? 32 : 64;
     __shared__ float As[TK][TM + 4];
     __shared__ float Bs[TK][TN + 4];
     __shared__ int64_t s_rows[MAX_BATCH];
     const int g = blockIdx.z, tid = threadIdx.x;
     const int64_t row0 = (int64_t)blockIdx.y * TM, col0 = (int64_t)blockIdx.x * TN;
     const int64_t R = p.rows(), C = p.cols(), K = p.depth();
-    const int lane = tid & 63, wm = tid >> 7, wn = (tid >> 6) & 1;
+    const int lane = tid & 63, wave = tid >> 6, wm = SMALL ? 0 : wave >> 1, wn = SMALL ? 0 : wave & 1;
     if (AK == IN_GATHER_F32 || AK == IN_GATHER_BF16) {
         const LayerInput in = p.input();
         for (int b = tid; b < in.B; b += GEMM_THREADS) s_rows[b] = in.row0[g] + in.idx[(size_t)g * in.B + b];
@@ -284,17 +288,31 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
         }
         __syncthreads();
         if (k0 + TK < K) fetch_step(k0 + TK);
+        constexpr int K_PER_WAVE = SMALL ? TK / 4 : TK;
 #pragma unroll
-        for (int kk = 0; kk < TK; kk += 2) {
-            const int k = kk + (lane >> 5);
+        for (int kk = 0; kk < K_PER_WAVE; kk += 2) {
+            const int k = (SMALL ? wave * K_PER_WAVE : 0) + kk + (lane >> 5);
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[k][32 * wm + (lane & 31)], Bs[k][32 * wn + (lane & 31)], acc, 0, 0, 0);
         }
     }
+    if constexpr (SMALL) {
+        __shared__ float part[4][32][33];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) part[wave][8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)][lane & 31] = acc[v];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = tid + j * GEMM_THREADS, r = e >> 5, c = e & 31;
+            const float sum = ((part[0][r][c] + part[1][r][c]) + part[2][r][c]) + part[3][r][c];
+            if (row0 + r < R && col0 + c < C) p.store(g, row0 + r, col0 + c, sum);
+        }
+    } else {
     const int64_t cc = col0 + 32 * wn + (lane & 31);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int64_t rr = row0 + 32 * wm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
         if (rr < R && cc < C) p.store(g, rr, cc, acc[v]);
+    }
     }
 }
 
@@ -394,9 +412,9 @@ static void launch_fwd_narrow(hipStream_t s, const FwdProblem &p, int kind, int 
     else launch_fwd_narrow_kind<32>(s, p, kind, grid);
 }
 
-template <class Problem> static dim3 gemm_grid(int groups, int64_t rows, int64_t cols)
+template <class Problem> static dim3 gemm_grid(int groups, int64_t rows, int64_t cols, int tile = 64)
 {
-    return dim3((unsigned)((cols + TN - 1) / TN), (unsigned)((rows + TM - 1) / TM), (unsigned)groups);
+    return dim3((unsigned)((cols + tile - 1) / tile), (unsigned)((rows + tile - 1) / tile), (unsigned)groups);
 }
 
 static void launch_gemm(hipStream_t s, const DgradProblem &p, int kind, int groups, int64_t rows, int64_t cols)
@@ -406,16 +424,26 @@ static void launch_gemm(hipStream_t s, const DgradProblem &p, int kind, int grou
     else hipLaunchKernelGGL((grouped_gemm_kernel<DgradProblem, IN_ACT_F32>), grid, dim3(GEMM_THREADS), 0, s, p);
 }
 
+// depth: the contraction length.  Few tiles and a long contraction (a small batch against a wide layer): the 32 x 32
+// variant, whose four waves share each step, puts four times as many workgroups on the chip.
 template <class Problem>
-static void launch_gemm(hipStream_t s, const Problem &p, int kind, int groups, int64_t rows, int64_t cols)
+static void launch_gemm(hipStream_t s, const Problem &p, int kind, int groups, int64_t rows, int64_t cols, int64_t depth)
 {
-    const dim3 grid = gemm_grid<Problem>(groups, rows, cols);
+    dim3 grid = gemm_grid<Problem>(groups, rows, cols);
+    const bool small = (int64_t)grid.x * grid.y * grid.z < 256 && depth >= 128;
+    if (small) grid = gemm_grid<Problem>(groups, rows, cols, 32);
+#define NETMAX_GEMM(KIND)                                                                                        \
+    do {                                                                                                         \
+        if (small) hipLaunchKernelGGL((grouped_gemm_kernel<Problem, KIND, true>), grid, dim3(GEMM_THREADS), 0, s, p);  \
+        else hipLaunchKernelGGL((grouped_gemm_kernel<Problem, KIND, false>), grid, dim3(GEMM_THREADS), 0, s, p);       \
+    } while (0)
     switch (kind) {
-    case IN_GATHER_F32: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_GATHER_F32>), grid, dim3(GEMM_THREADS), 0, s, p); break;
-    case IN_GATHER_BF16: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_GATHER_BF16>), grid, dim3(GEMM_THREADS), 0, s, p); break;
-    case IN_ACT_F32: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_ACT_F32>), grid, dim3(GEMM_THREADS), 0, s, p); break;
-    default: hipLaunchKernelGGL((grouped_gemm_kernel<Problem, IN_ACT_BF16>), grid, dim3(GEMM_THREADS), 0, s, p); break;
+    case IN_GATHER_F32: NETMAX_GEMM(IN_GATHER_F32); break;
+    case IN_GATHER_BF16: NETMAX_GEMM(IN_GATHER_BF16); break;
+    case IN_ACT_F32: NETMAX_GEMM(IN_ACT_F32); break;
+    default: NETMAX_GEMM(IN_ACT_BF16); break;
     }
+#undef NETMAX_GEMM
 }
 
 // Softmax cross-entropy on the logits: dz = (softmax - onehot) / B and the mean loss per worker.
@@ -538,7 +566,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
         f.out_bf16_t = (bf && !last) ? p.ht[l + 1] : nullptr;
         // few outputs: the tiled kernel would pad them to a 64-column tile on one workgroup per worker
         if (f.dout <= 32) launch_fwd_narrow(s, f, f.in.kind, p.M);
-        else launch_gemm(s, f, f.in.kind, p.M, p.B, f.dout);
+        else launch_gemm(s, f, f.in.kind, p.M, p.B, f.dout, f.din);
     }
     // loss and dZ of the last layer
     const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
@@ -561,7 +589,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
             WgradProblem wg;
             wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;
             wg.B = p.B; wg.G = G;
-            launch_gemm(s, wg, wg.in.kind, p.M, din, dout);
+            launch_gemm(s, wg, wg.in.kind, p.M, din, dout, p.B);
         }
         if (!bias_done[l]) {
             hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((dout + 63) / 64), (unsigned)p.M), dim3(256), 0, s, p.M, p.B,

@@ -180,6 +180,11 @@ GRAD_CASES = [
     ("cfg2", dict(M=3, batch=37, n_per_worker=60, dims=(40, 600, 27))),
     ("cfg5", dict(M=3, batch=19, n_per_worker=50, dims=(30, 450, 12))),
     ("cfg5", dict(M=2, batch=20, n_per_worker=50, dims=(400, 5))),
+    # few tiles and a long contraction (the 32 x 32 tiles whose waves share each step): forward with every input
+    # kind, weight gradient with a batch of at least 128, ragged edges
+    ("cfg2", dict(M=3, batch=50, n_per_worker=80, dims=(200, 150, 130, 7))),
+    ("cfg5", dict(M=3, batch=37, n_per_worker=60, dims=(300, 90, 140, 40, 6))),
+    ("cfg2", dict(M=2, batch=130, n_per_worker=200, dims=(40, 50, 10))),
 ]
 
 # Gradient tolerances, relative L2 per worker.  fp32 operands: fp32 accumulation over at most a few
