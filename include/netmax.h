@@ -221,6 +221,21 @@ int netmax_update_times_async(netmax_ctx *ctx, const int32_t *active_dev, const 
  * order.  Waits for the stream; out_host: host double. */
 int netmax_consensus_dist(netmax_ctx *ctx, double *out_host);
 
+/* The consensus distance for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Needs no context and calls no allocator: the per-block partial
+ * sums that netmax_consensus_dist keeps in context-owned memory live in a fixed device array inside the library
+ * (NETMAX_STATIC_PARTIALS doubles = 512 KB per GPU, held until the process ends), so ld may be at most
+ * NETMAX_STATIC_MAX_LD columns; a longer matrix is rejected with NETMAX_EINVAL (text: netmax_last_error(NULL)).
+ * x_dev: device float M x ld in the tile layout (ld a multiple of NETMAX_TILE, 16-byte aligned, 1 <= D <= ld,
+ * 2 <= M <= 4096); cd_dev: device double [1], caller-owned, receives the same value netmax_consensus_dist returns
+ * (same kernels, same summation order); stream: hipStream_t on the current device, NULL = the null stream.
+ * Enqueues two kernels and returns without waiting.  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (different streams, or graphs replayed side by side) race and must be serialised
+ * by the caller.  Nothing has to be cleared between calls: every partial sum read is written by the same call. */
+#define NETMAX_STATIC_PARTIALS 65536
+#define NETMAX_STATIC_MAX_LD ((int64_t)NETMAX_STATIC_PARTIALS * 1024)
+int netmax_consensus_dist_static(int32_t M, int64_t D, int64_t ld, const float *x_dev, double *cd_dev, void *stream);
+
 /* Device pointer of the current parameters x^t (one of x_a, x_b; tile layout), NULL if nothing is bound. */
 const float *netmax_params(const netmax_ctx *ctx);
 

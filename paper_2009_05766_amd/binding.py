@@ -15,6 +15,8 @@ LIB_PATH = os.path.join(_PKG, "libnetmax.so")
 
 NETMAX_MAX_LAYERS = 7
 NETMAX_TILE = 2048
+NETMAX_STATIC_PARTIALS = 65536
+NETMAX_STATIC_MAX_LD = NETMAX_STATIC_PARTIALS * 1024
 NETMAX_OK, NETMAX_EINVAL, NETMAX_EINFEASIBLE, NETMAX_ESTATE, NETMAX_EDEVICE, NETMAX_ENOMEM = range(6)
 NETMAX_FLAT, NETMAX_MLP = 0, 1
 NETMAX_F32, NETMAX_BF16 = 0, 1
@@ -23,7 +25,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
     "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_update_times_async", "netmax_activity", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
-    "netmax_consensus_dist", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
+    "netmax_consensus_dist", "netmax_consensus_dist_static", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
 
@@ -85,6 +87,7 @@ def load():
         "netmax_set_activity": (C.c_int, [vp, vp]),
         "netmax_async_run": (C.c_int, [vp, C.c_uint64, C.c_uint64, vp, vp]),
         "netmax_consensus_dist": (C.c_int, [vp, C.POINTER(C.c_double)]),
+        "netmax_consensus_dist_static": (C.c_int, [i32, i64, i64, vp, vp, vp]),
         "netmax_params": (vp, [vp]),
         "netmax_losses": (vp, [vp]),
         "netmax_iteration": (u64, [vp]),
@@ -277,6 +280,12 @@ def netmax_consensus_dist(ctx) -> float:
     out = C.c_double()
     _check(load().netmax_consensus_dist(ctx, C.byref(out)), ctx)
     return out.value
+
+
+def netmax_consensus_dist_static(M: int, D: int, ld: int, x, cd, stream: int = 0):
+    """x: device float tensor (tile layout), cd: device float64 tensor [1]; enqueues on `stream`, allocates nothing."""
+    import torch
+    _check(load().netmax_consensus_dist_static(M, D, ld, _dp(x, torch.float32), _dp(cd, torch.float64), stream))
 
 
 def netmax_params(ctx) -> int:

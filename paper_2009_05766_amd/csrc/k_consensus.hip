@@ -9,6 +9,7 @@ namespace netmax {
 
 constexpr int CD_THREADS = 256;
 constexpr int CD_COLS = CD_THREADS * 4;
+static_assert(CD_COLS == CONSENSUS_COLS, "one partial sum per CONSENSUS_COLS columns");
 static_assert(TILE % CD_COLS == 0, "a workgroup stays inside one tile");
 
 int consensus_partials(int64_t ld) { return (int)((ld + CD_COLS - 1) / CD_COLS); }

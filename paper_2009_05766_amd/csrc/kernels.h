@@ -61,7 +61,8 @@ void launch_mix_subset(hipStream_t s, int M, const int32_t *tiles, int n_listed,
                        float wd);
 
 // Consensus distance: per-block partial sums (double), then a fixed-order final sum into out_dev[0].
-// partial must hold consensus_partials(ld) doubles.
+// partial must hold consensus_partials(ld) doubles: one per CONSENSUS_COLS columns.
+constexpr int CONSENSUS_COLS = 1024;
 int consensus_partials(int64_t ld);
 void launch_consensus(hipStream_t s, int M, int64_t D, int64_t ld, const float *X, double *partial,
                       double *out_dev);

@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -800,6 +801,54 @@ extern "C" int netmax_consensus_dist(netmax_ctx *ctx, double *out_host)
     HIP_TRY(ctx, hipMemcpyAsync(out_host, ctx->d_cd, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return NETMAX_OK;
+}
+
+// ---- consensus distance without any allocation ------------------------------------------------------------
+// The partial sums live in a fixed device array.  In host code the array's name is only a handle for the symbol
+// lookup: its device address differs per GPU, is asked for once per device and kept; kernels get that address.
+static_assert((int64_t)NETMAX_STATIC_PARTIALS * CONSENSUS_COLS == NETMAX_STATIC_MAX_LD, "header limits must agree");
+static __device__ __align__(256) double scratch[NETMAX_STATIC_PARTIALS];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static double *g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+static int scratch_of_current_device(double **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(nullptr, NETMAX_EDEVICE, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(nullptr, NETMAX_EDEVICE, "device index out of range");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(nullptr, NETMAX_EDEVICE, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+        g_scratch_ptr[dev] = (double *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_consensus_dist_static(int32_t M, int64_t D, int64_t ld, const float *x_dev, double *cd_dev, void *stream)
+{
+    if (!x_dev || !cd_dev) return fail(nullptr, NETMAX_EINVAL, "x_dev or cd_dev is NULL");
+    if (M < 2 || M > 4096) return fail(nullptr, NETMAX_EINVAL, "M must be in 2..4096");
+    if (D < 1 || ld < D || ld % TILE != 0) return fail(nullptr, NETMAX_EINVAL, "need 1 <= D <= ld and ld a multiple of NETMAX_TILE");
+    if ((uintptr_t)x_dev % 16 != 0 || (uintptr_t)cd_dev % 8 != 0) return fail(nullptr, NETMAX_EINVAL, "x_dev must be 16-byte and cd_dev 8-byte aligned");
+    if (ld > NETMAX_STATIC_MAX_LD || consensus_partials(ld) > NETMAX_STATIC_PARTIALS) {
+        char buf[160];
+        snprintf(buf, sizeof buf, "ld = %lld exceeds NETMAX_STATIC_MAX_LD = %lld columns (the fixed scratch array)",
+                 (long long)ld, (long long)NETMAX_STATIC_MAX_LD);
+        return fail(nullptr, NETMAX_EINVAL, buf);
+    }
+    double *partial = nullptr;
+    const int rc = scratch_of_current_device(&partial);
+    if (rc != NETMAX_OK) return rc;
+    launch_consensus((hipStream_t)stream, M, D, ld, x_dev, partial, cd_dev);
+    return check_launch(nullptr, "consensus (static scratch)");
 }
 
 extern "C" const float *netmax_params(const netmax_ctx *ctx) { return ctx ? ctx->x_cur : nullptr; }
