@@ -242,6 +242,17 @@ const float *netmax_params(const netmax_ctx *ctx);
 /* MLP only: device float [M], mean batch loss of each worker as computed by the last netmax_local_step. */
 const float *netmax_losses(const netmax_ctx *ctx);
 
+/* MLP only: copies those M losses to out_dev (device float [M], caller-owned) on the context's stream; returns
+ * without waiting. */
+int netmax_read_losses(netmax_ctx *ctx, float *out_dev);
+
+/* MLP only: the outputs of hidden layer `layer` (1 .. n_layers - 1; the ReLU outputs that feed layer `layer` + 1) of
+ * the last netmax_local_step, as device float [M][batch][dims[layer]] into out_dev (caller-owned), on the context's
+ * stream, without waiting.  With bf16 operands these are the stored bfloat16 activations, widened.  An entry is
+ * positive exactly where the backward pass took the ReLU derivative as 1 (Algorithm 2's stochastic gradient is
+ * discontinuous there, which is what run-to-run comparisons look at). */
+int netmax_read_hidden(netmax_ctx *ctx, int32_t layer, float *out_dev);
+
 /* Number of netmax_mix calls so far (the next iteration's default counter). */
 uint64_t netmax_iteration(const netmax_ctx *ctx);
 

@@ -165,6 +165,48 @@ def local_grad(dims: Sequence[int], X: np.ndarray, feats: np.ndarray, labels: np
     return G, loss
 
 
+def hidden_mlp(dims: Sequence[int], params: np.ndarray, feats: np.ndarray, idx: np.ndarray,
+               operands_bf16: bool = False):
+    """One worker: the pre-activations of the hidden layers on the batch, as a list of float64 [B, dims[l+1]]."""
+    d = np.asarray(dims, dtype=np.int64)
+    nl = len(dims) - 1
+    bf16 = feats.dtype == np.uint16
+    assert bf16 or feats.dtype == np.float32
+    assert feats.flags.c_contiguous and feats.shape[1] == dims[0]
+    idx = _chk(idx, np.int32)
+    B = idx.shape[0]
+    z = np.empty(B * int(sum(dims[1:nl])), dtype=np.float64)
+    lib().ora_hidden_mlp(C.c_int(nl), _p(d), _p(_chk(params, np.float32)), _p(feats), C.c_int(int(bf16)),
+                         C.c_int(int(operands_bf16)), _p(idx), C.c_int(B), _p(z))
+    out, o = [], 0
+    for l in range(1, nl):
+        out.append(z[o:o + B * dims[l]].reshape(B, dims[l]))
+        o += B * dims[l]
+    return out
+
+
+def local_hidden(dims: Sequence[int], X: np.ndarray, feats: np.ndarray, shard_off: np.ndarray, idx: np.ndarray,
+                 operands_bf16: bool = False):
+    """All workers: list over hidden layers of float64 [M, B, dims[l+1]] pre-activations."""
+    d = np.asarray(dims, dtype=np.int64)
+    nl = len(dims) - 1
+    M, ld = X.shape
+    B = idx.shape[1]
+    bf16 = feats.dtype == np.uint16
+    assert bf16 or feats.dtype == np.float32
+    assert feats.flags.c_contiguous and feats.shape[1] == dims[0]
+    per = B * int(sum(dims[1:nl]))
+    Z = np.empty((M, per), dtype=np.float64)
+    lib().ora_local_hidden(C.c_int(M), C.c_int64(ld), C.c_int(nl), _p(d), _p(_chk(X, np.float32)), _p(feats),
+                           C.c_int(int(bf16)), C.c_int(int(operands_bf16)), _p(_chk(shard_off, np.int64)),
+                           _p(_chk(idx, np.int32)), C.c_int(B), _p(Z))
+    out, o = [], 0
+    for l in range(1, nl):
+        out.append(Z[:, o:o + B * dims[l]].reshape(M, B, dims[l]))
+        o += B * dims[l]
+    return out
+
+
 def mix(Xcur: np.ndarray, G: np.ndarray, V: np.ndarray, peer: np.ndarray, w: np.ndarray,
         alpha: float, mu: float, wd: float = 0.0, out: Optional[np.ndarray] = None,
         convex_form: bool = False) -> np.ndarray:

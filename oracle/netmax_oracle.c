@@ -251,44 +251,76 @@ double ora_round_bf16(double x)
 
 static inline double opnd(double x, int bf16) { return bf16 ? ora_round_bf16(x) : x; }
 
+/* The operands of a matrix product as the chosen arithmetic sees them: n values, each rounded to bfloat16 when
+ * rb != 0, as doubles (rounding is a function of the element alone, so it is done once per matrix here instead of
+ * once per use; the products and their order are unchanged). */
+static double *operands_f32(const float *x, size_t n, int rb)
+{
+    double *r = (double *)malloc(sizeof(double) * (n ? n : 1));
+    for (size_t k = 0; k < n; ++k) r[k] = opnd((double)x[k], rb);
+    return r;
+}
+
+static double *operands_f64(const double *x, size_t n, int rb)
+{
+    double *r = (double *)malloc(sizeof(double) * (n ? n : 1));
+    for (size_t k = 0; k < n; ++k) r[k] = opnd(x[k], rb);
+    return r;
+}
+
+/* Forward pass of one worker's batch.  a[0] = the batch rows, a[l] = ReLU output of layer l-1, a[n_layers] = logits;
+ * Wop[l] = layer l's weights as operands.  z_hidden (may be NULL) receives the pre-activations of the hidden layers,
+ * layer after layer, each [B][dims[l+1]]. */
+static void forward_mlp(int n_layers, const int64_t *dims, const float *params, const void *feats, int feats_bf16,
+                        int rb, const int32_t *idx, int B, double **a, double **Wop, size_t *woff, double *z_hidden)
+{
+    const int64_t d0 = dims[0];
+    for (int b = 0; b < B; ++b)
+        for (int64_t k = 0; k < d0; ++k)
+            a[0][(size_t)b * d0 + k] = feat_at(feats, feats_bf16, (size_t)idx[b] * d0 + k);
+    size_t off = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int64_t din = dims[l], dout = dims[l + 1];
+        const float *W = params + off, *bias = W + din * dout;
+        woff[l] = off;
+        off += (size_t)(din * dout + dout);
+        Wop[l] = operands_f32(W, (size_t)(din * dout), rb);
+        double *xin = operands_f64(a[l], (size_t)B * din, rb);
+        for (int b = 0; b < B; ++b) {
+            double *z = a[l + 1] + (size_t)b * dout;
+            for (int64_t o = 0; o < dout; ++o) z[o] = 0.0;
+            for (int64_t k = 0; k < din; ++k) {
+                const double x = xin[(size_t)b * din + k];
+                const double *Wk = Wop[l] + k * dout;
+                for (int64_t o = 0; o < dout; ++o) z[o] += x * Wk[o];
+            }
+            for (int64_t o = 0; o < dout; ++o) z[o] += (double)bias[o];
+            if (l + 1 < n_layers) {
+                if (z_hidden) {
+                    for (int64_t o = 0; o < dout; ++o) z_hidden[(size_t)b * dout + o] = z[o];
+                }
+                for (int64_t o = 0; o < dout; ++o) z[o] = z[o] > 0.0 ? z[o] : 0.0;
+            }
+        }
+        if (z_hidden && l + 1 < n_layers) z_hidden += (size_t)B * dout;
+        free(xin);
+    }
+}
+
 double ora_grad_mlp(int n_layers, const int64_t *dims, const float *params, const void *feats, int feats_bf16,
                     int operands_bf16, const int32_t *labels, const int32_t *idx, int B, float *grad)
 {
     const int rb = operands_bf16;
     int64_t maxw = 0;
     for (int l = 0; l <= n_layers; ++l) if (dims[l] > maxw) maxw = dims[l];
-    /* a[l] = input of layer l (a[0] = data rows, a[l] = ReLU output of layer l-1), a[n_layers] = logits */
     double **a = (double **)malloc(sizeof(double *) * (n_layers + 1));
     for (int l = 0; l <= n_layers; ++l) a[l] = (double *)malloc(sizeof(double) * B * dims[l]);
+    double **Wop = (double **)malloc(sizeof(double *) * n_layers);
+    size_t *woff = (size_t *)malloc(sizeof(size_t) * n_layers);
     double *dz = (double *)malloc(sizeof(double) * B * maxw);
     double *da = (double *)malloc(sizeof(double) * B * maxw);
-    double *wr = (double *)malloc(sizeof(double) * maxw);
-    const int64_t d0 = dims[0];
-    for (int b = 0; b < B; ++b)
-        for (int64_t k = 0; k < d0; ++k)
-            a[0][(size_t)b * d0 + k] = feat_at(feats, feats_bf16, (size_t)idx[b] * d0 + k);
+    forward_mlp(n_layers, dims, params, feats, feats_bf16, rb, idx, B, a, Wop, woff, NULL);
 
-    /* forward */
-    size_t off = 0;
-    size_t *woff = (size_t *)malloc(sizeof(size_t) * n_layers);
-    for (int l = 0; l < n_layers; ++l) {
-        const int64_t din = dims[l], dout = dims[l + 1];
-        const float *W = params + off, *bias = W + din * dout;
-        woff[l] = off;
-        off += (size_t)(din * dout + dout);
-        for (int b = 0; b < B; ++b) {
-            double *z = a[l + 1] + (size_t)b * dout;
-            for (int64_t o = 0; o < dout; ++o) z[o] = 0.0;
-            for (int64_t k = 0; k < din; ++k) {
-                const double x = opnd(a[l][(size_t)b * din + k], rb);
-                const float *Wk = W + k * dout;
-                for (int64_t o = 0; o < dout; ++o) z[o] += x * opnd((double)Wk[o], rb);
-            }
-            for (int64_t o = 0; o < dout; ++o) z[o] += (double)bias[o];
-            if (l + 1 < n_layers)
-                for (int64_t o = 0; o < dout; ++o) z[o] = z[o] > 0.0 ? z[o] : 0.0;
-        }
-    }
     /* softmax cross-entropy, mean over the batch */
     const int64_t C = dims[n_layers];
     double loss = 0.0;
@@ -306,16 +338,17 @@ double ora_grad_mlp(int n_layers, const int64_t *dims, const float *params, cons
     /* backward */
     for (int l = n_layers - 1; l >= 0; --l) {
         const int64_t din = dims[l], dout = dims[l + 1];
-        const float *W = params + woff[l];
         float *gW = grad + woff[l], *gb = gW + din * dout;
         double *acc = (double *)calloc((size_t)dout, sizeof(double));
+        double *xin = operands_f64(a[l], (size_t)B * din, rb);
+        double *dzo = operands_f64(dz, (size_t)B * dout, rb);
         /* gW = a_l^T dz */
         for (int64_t k = 0; k < din; ++k) {
             memset(acc, 0, sizeof(double) * dout);
             for (int b = 0; b < B; ++b) {
-                const double x = opnd(a[l][(size_t)b * din + k], rb);
-                const double *d = dz + (size_t)b * dout;
-                for (int64_t o = 0; o < dout; ++o) acc[o] += x * opnd(d[o], rb);
+                const double x = xin[(size_t)b * din + k];
+                const double *d = dzo + (size_t)b * dout;
+                for (int64_t o = 0; o < dout; ++o) acc[o] += x * d[o];
             }
             for (int64_t o = 0; o < dout; ++o) gW[k * dout + o] = (float)acc[o];
         }
@@ -328,21 +361,53 @@ double ora_grad_mlp(int n_layers, const int64_t *dims, const float *params, cons
         if (l > 0) {
             /* da = dz W^T, then through the ReLU: derivative 1 where the activation is positive, else 0 */
             for (int b = 0; b < B; ++b) {
-                const double *d = dz + (size_t)b * dout;
-                for (int64_t o = 0; o < dout; ++o) wr[o] = opnd(d[o], rb);
+                const double *d = dzo + (size_t)b * dout;
                 for (int64_t k = 0; k < din; ++k) {
-                    const float *Wk = W + k * dout;
+                    const double *Wk = Wop[l] + k * dout;
                     double s = 0.0;
-                    for (int64_t o = 0; o < dout; ++o) s += wr[o] * opnd((double)Wk[o], rb);
+                    for (int64_t o = 0; o < dout; ++o) s += d[o] * Wk[o];
                     da[(size_t)b * din + k] = a[l][(size_t)b * din + k] > 0.0 ? s : 0.0;
                 }
             }
             double *t = dz; dz = da; da = t;
         }
+        free(xin); free(dzo);
     }
     for (int l = 0; l <= n_layers; ++l) free(a[l]);
-    free(a); free(dz); free(da); free(wr); free(woff);
+    for (int l = 0; l < n_layers; ++l) free(Wop[l]);
+    free(a); free(Wop); free(dz); free(da); free(woff);
     return loss;
+}
+
+/* The pre-activations z = a W + b of the hidden layers of one worker's batch, in the arithmetic ora_grad_mlp uses:
+ * z_hidden receives layer after layer, each [B][dims[l+1]] (l = 0 .. n_layers-2).  Their signs are the ReLU
+ * decisions of the gradient; the tests count where another implementation decides differently. */
+void ora_hidden_mlp(int n_layers, const int64_t *dims, const float *params, const void *feats, int feats_bf16,
+                    int operands_bf16, const int32_t *idx, int B, double *z_hidden)
+{
+    double **a = (double **)malloc(sizeof(double *) * (n_layers + 1));
+    for (int l = 0; l <= n_layers; ++l) a[l] = (double *)malloc(sizeof(double) * B * dims[l]);
+    double **Wop = (double **)malloc(sizeof(double *) * n_layers);
+    size_t *woff = (size_t *)malloc(sizeof(size_t) * n_layers);
+    forward_mlp(n_layers, dims, params, feats, feats_bf16, operands_bf16, idx, B, a, Wop, woff, z_hidden);
+    for (int l = 0; l <= n_layers; ++l) free(a[l]);
+    for (int l = 0; l < n_layers; ++l) free(Wop[l]);
+    free(a); free(Wop); free(woff);
+}
+
+/* All workers' hidden pre-activations: Z is [M][sum over hidden layers of B * dims[l+1]]. */
+void ora_local_hidden(int M, int64_t ld, int n_layers, const int64_t *dims, const float *X, const void *feats,
+                      int feats_bf16, int operands_bf16, const int64_t *shard_off, const int32_t *idx, int B, double *Z)
+{
+    size_t per = 0;
+    for (int l = 0; l + 1 < n_layers; ++l) per += (size_t)B * dims[l + 1];
+    const size_t esz = feats_bf16 ? 2 : 4;
+#pragma omp parallel for num_threads(g_threads) schedule(dynamic, 1)
+    for (int i = 0; i < M; ++i) {
+        const char *f = (const char *)feats + (size_t)shard_off[i] * dims[0] * esz;
+        ora_hidden_mlp(n_layers, dims, X + (size_t)i * ld, f, feats_bf16, operands_bf16, idx + (size_t)i * B, B,
+                       Z + (size_t)i * per);
+    }
 }
 
 /* All workers: gradient of worker i from row i of X into row i of G (padding columns set to 0).

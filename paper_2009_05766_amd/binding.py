@@ -25,7 +25,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
     "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_update_times_async", "netmax_activity", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
-    "netmax_consensus_dist", "netmax_consensus_dist_static", "netmax_params", "netmax_losses", "netmax_iteration", "netmax_get_tables",
+    "netmax_consensus_dist", "netmax_consensus_dist_static", "netmax_params", "netmax_losses", "netmax_read_losses", "netmax_read_hidden", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
 
@@ -90,6 +90,8 @@ def load():
         "netmax_consensus_dist_static": (C.c_int, [i32, i64, i64, vp, vp, vp]),
         "netmax_params": (vp, [vp]),
         "netmax_losses": (vp, [vp]),
+        "netmax_read_losses": (C.c_int, [vp, vp]),
+        "netmax_read_hidden": (C.c_int, [vp, i32, vp]),
         "netmax_iteration": (u64, [vp]),
         "netmax_get_tables": (C.c_int, [vp, vp, vp, vp]),
         "netmax_last_error": (C.c_char_p, [vp]),
@@ -296,6 +298,16 @@ def netmax_losses(ctx) -> int:
     return load().netmax_losses(ctx) or 0
 
 
+def netmax_read_losses(ctx, out):
+    import torch
+    _check(load().netmax_read_losses(ctx, _dp(out, torch.float32)), ctx)
+
+
+def netmax_read_hidden(ctx, layer: int, out):
+    import torch
+    _check(load().netmax_read_hidden(ctx, layer, _dp(out, torch.float32)), ctx)
+
+
 def netmax_iteration(ctx) -> int:
     return int(load().netmax_iteration(ctx))
 
@@ -325,7 +337,7 @@ class NetMax:
                  mix_mode=NETMAX_MIX_POLICY, fixed_weight=0.5, X0: Optional[np.ndarray] = None, feats=None, labels=None, shard_off=None, device="cuda:0"):
         import torch
         assert ld % NETMAX_TILE == 0, "ld must be a multiple of NETMAX_TILE"
-        self.M, self.D, self.ld, self.batch = M, D, ld, batch
+        self.M, self.D, self.ld, self.batch, self.dims = M, D, ld, batch, tuple(dims)
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self._own = torch.cuda.current_stream(self.device)     # the stream every library call of this run uses
@@ -429,16 +441,21 @@ class NetMax:
     def losses(self):
         """Mean batch loss per worker of the last local step (device tensor [M]), None for flat models."""
         import torch
-        p = netmax_losses(self.ctx)
-        if not p:
+        if not netmax_losses(self.ctx):
             return None
         out = torch.empty(self.M, dtype=torch.float32, device=self.device)
-        hip = C.CDLL("libamdhip64.so")
         self._join()
-        self._own.synchronize()
-        rc = hip.hipMemcpy(C.c_void_p(out.data_ptr()), C.c_void_p(p), C.c_size_t(4 * self.M), C.c_int(3))
-        if rc != 0:
-            raise RuntimeError(f"hipMemcpy of the loss vector failed with {rc}")
+        netmax_read_losses(self.ctx, out)
+        self._join()
+        return out
+
+    def hidden(self, layer: int):
+        """Outputs of hidden layer `layer` of the last local step, device tensor [M, batch, dims[layer]]."""
+        import torch
+        out = torch.empty((self.M, self.batch, self.dims[layer]), dtype=torch.float32, device=self.device)
+        self._join()
+        netmax_read_hidden(self.ctx, layer, out)
+        self._join()
         return out
 
     def close(self):

@@ -28,6 +28,18 @@ __global__ void __launch_bounds__(256) unpack_kernel(int M, int64_t cols, const 
     rows[(size_t)i * row_ld + j] = tiled[tiled_offset(M, i, j)];
 }
 
+// out[k] = the bfloat16 value in[k] widened to float.
+__global__ void __launch_bounds__(256) widen_bf16_kernel(int64_t n, const uint16_t *__restrict__ in, float *__restrict__ out)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < n) out[k] = __uint_as_float((uint32_t)in[k] << 16);
+}
+
+void launch_widen_bf16(hipStream_t s, int64_t n, const uint16_t *in, float *out)
+{
+    hipLaunchKernelGGL(widen_bf16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, in, out);
+}
+
 void launch_pack(hipStream_t s, int M, int64_t cols, int64_t ld, const float *rows, int64_t row_ld, float *tiled)
 {
     const int64_t n = (int64_t)M * ld;

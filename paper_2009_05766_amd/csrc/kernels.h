@@ -71,6 +71,9 @@ void launch_consensus(hipStream_t s, int M, int64_t D, int64_t ld, const float *
 void launch_pack(hipStream_t s, int M, int64_t cols, int64_t ld, const float *rows, int64_t row_ld, float *tiled);
 void launch_unpack(hipStream_t s, int M, int64_t cols, const float *tiled, float *rows, int64_t row_ld);
 
+// out[k] = bfloat16 in[k] as float, k < n.
+void launch_widen_bf16(hipStream_t s, int64_t n, const uint16_t *in, float *out);
+
 // Per-worker MLP / softmax-regression gradient (grouped GEMMs).
 struct MlpPlan {
     int M, n_layers, B;

@@ -853,6 +853,32 @@ extern "C" int netmax_consensus_dist_static(int32_t M, int64_t D, int64_t ld, co
 
 extern "C" const float *netmax_params(const netmax_ctx *ctx) { return ctx ? ctx->x_cur : nullptr; }
 extern "C" const float *netmax_losses(const netmax_ctx *ctx) { return ctx ? ctx->d_loss : nullptr; }
+
+extern "C" int netmax_read_losses(netmax_ctx *ctx, float *out_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (ctx->cfg.model != NETMAX_MLP) return fail(ctx, NETMAX_ESTATE, "only perceptron models have losses");
+    if (!out_dev) return fail(ctx, NETMAX_EINVAL, "out_dev is NULL");
+    HIP_TRY(ctx, hipMemcpyAsync(out_dev, ctx->d_loss, (size_t)ctx->cfg.M * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_read_hidden(netmax_ctx *ctx, int32_t layer, float *out_dev)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    const netmax_config &c = ctx->cfg;
+    if (c.model != NETMAX_MLP) return fail(ctx, NETMAX_ESTATE, "only perceptron models have hidden layers");
+    if (layer < 1 || layer >= c.n_layers) return fail(ctx, NETMAX_EINVAL, "layer must be in 1 .. n_layers - 1");
+    if (!out_dev) return fail(ctx, NETMAX_EINVAL, "out_dev is NULL");
+    const int64_t n = (int64_t)c.M * c.batch * c.dims[layer];
+    if (c.gemm_in == NETMAX_BF16) {
+        launch_widen_bf16(ctx->stream, n, ctx->d_hb[layer], out_dev);
+        return check_launch(ctx, "read_hidden");
+    }
+    HIP_TRY(ctx, hipMemcpyAsync(out_dev, ctx->d_act[layer], (size_t)n * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+    return NETMAX_OK;
+}
+
 extern "C" uint64_t netmax_iteration(const netmax_ctx *ctx) { return ctx ? ctx->iterations : 0; }
 
 extern "C" int netmax_get_tables(netmax_ctx *ctx, uint32_t *thresholds_host, int32_t *last_host, float *w_host)

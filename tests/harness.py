@@ -47,3 +47,30 @@ def rel_err_rows(a: np.ndarray, b: np.ndarray) -> float:
     num = np.sqrt(((a - b) ** 2).sum(axis=1))
     den = np.maximum(np.sqrt((b ** 2).sum(axis=1)), 1e-30)
     return float((num / den).max())
+
+
+def max_abs_err(a: np.ndarray, b: np.ndarray) -> float:
+    """Largest element-wise difference |a - b| (computed in double)."""
+    return float(np.abs(a.astype(np.float64) - b.astype(np.float64)).max()) if a.size else 0.0
+
+
+def compare_on_device(got_dev, want_host: np.ndarray, slab: int = 1 << 20):
+    """Element-by-element comparison of a device matrix [M, n] with the oracle's host matrix, done with torch on
+    the device in double, slab by slab (test arithmetic only).  -> (max over rows of ||got_i - want_i|| / ||want_i||,
+    max |got - want|, max |want|)."""
+    import torch
+    want = torch.from_numpy(want_host).to(got_dev.device)
+    assert want.shape == got_dev.shape
+    M, n = want.shape
+    num = torch.zeros(M, dtype=torch.float64, device=want.device)
+    den = torch.zeros_like(num)
+    worst = ref = 0.0
+    for c in range(0, n, slab):
+        a, b = got_dev[:, c:c + slab].double(), want[:, c:c + slab].double()
+        d = a - b
+        num += (d * d).sum(1)
+        den += (b * b).sum(1)
+        worst = max(worst, float(d.abs().max()))
+        ref = max(ref, float(b.abs().max()))
+    rel = float((num.sqrt() / den.sqrt().clamp_min(1e-30)).max())
+    return rel, worst, ref

@@ -160,3 +160,43 @@ def test_bf16_operand_mode_matches_torch_autograd_with_bf16_cast_products(ora, d
     # and it differs measurably from the exact-arithmetic gradient
     g_exact, _ = ora.grad_mlp(dims, params, feats, labels, idx)
     assert 1e-4 < np.linalg.norm(g - g_exact) / np.linalg.norm(g_exact) < 0.1
+
+
+@pytest.mark.parametrize("dims,bf16", [((6, 5, 4), False), ((7, 6, 5, 3), False), ((20, 16, 12, 6), True)])
+def test_hidden_pre_activations_match_torch(ora, dims, bf16):
+    """ora_hidden_mlp against a forward pass written with torch (fp64 matmuls; in the bf16 mode both operands of
+    every product cast by torch): layer order, bias included, value before the ReLU."""
+    rng = np.random.default_rng(5 + sum(dims))
+    params, feats, labels, idx = _problem(rng, dims, 40, 11, bf16=bf16)
+    zs = ora.hidden_mlp(dims, params, feats, idx, operands_bf16=bf16)
+    assert len(zs) == len(dims) - 2
+    r = (lambda t: t.to(torch.float32).to(torch.bfloat16).to(torch.float64)) if bf16 else (lambda t: t)
+    p = torch.tensor(params, dtype=torch.float64)
+    a = torch.tensor((bf16_bits_to_f32(feats) if bf16 else feats)[idx], dtype=torch.float64)
+    o = 0
+    for l in range(len(dims) - 2):
+        W = p[o:o + dims[l] * dims[l + 1]].reshape(dims[l], dims[l + 1])
+        o += dims[l] * dims[l + 1]
+        b = p[o:o + dims[l + 1]]
+        o += dims[l + 1]
+        z = r(a) @ r(W) + b
+        assert zs[l].shape == (11, dims[l + 1])
+        np.testing.assert_allclose(zs[l], z.numpy(), rtol=1e-12, atol=1e-13)
+        assert (zs[l] < 0).any() and (zs[l] > 0).any()
+        a = torch.relu(z)
+
+
+def test_all_workers_hidden_wrapper(ora):
+    rng = np.random.default_rng(41)
+    dims, M, B = (6, 5, 4, 3), 3, 5
+    D = sum(dims[l] * dims[l + 1] + dims[l + 1] for l in range(3))
+    shard_off = np.array([0, 7, 19, 30], dtype=np.int64)
+    feats = rng.standard_normal((30, 6)).astype(np.float32)
+    X = np.zeros((M, 128), np.float32)
+    X[:, :D] = rng.standard_normal((M, D)) * 0.3
+    idx = ora.sample_batch(M, B, shard_off, 3, 0)
+    Z = ora.local_hidden(dims, X, feats, shard_off, idx)
+    for i in range(M):
+        zs = ora.hidden_mlp(dims, X[i], feats[shard_off[i]:shard_off[i + 1]], idx[i])
+        for l in range(2):
+            assert np.array_equal(Z[l][i], zs[l])

@@ -45,8 +45,13 @@ MUTANTS = [
     ("test_oracle_grad.py", C, "gb[o] = (float)acc[o];", "gb[o] = 0.0f;"),
     ("test_oracle_grad.py", C, "b += 0x7FFFu + ((b >> 16) & 1u);", "b += 0x8000u;"),
     ("test_oracle_grad.py", C, "z[o] = z[o] > 0.0 ? z[o] : 0.0;", "z[o] = z[o] > 0.0 ? z[o] : 0.01 * z[o];"),
-    ("test_oracle_grad.py", C, "for (int64_t o = 0; o < dout; ++o) s += wr[o] * opnd((double)Wk[o], rb);",
-     "for (int64_t o = 0; o < dout; ++o) s += wr[o] * opnd((double)W[o * din + k], rb);"),
+    ("test_oracle_grad.py", C, "for (int64_t o = 0; o < dout; ++o) s += d[o] * Wk[o];",
+     "for (int64_t o = 0; o < dout; ++o) s += d[o] * Wop[l][o * din + k];"),
+    ("test_oracle_grad.py", C, "for (size_t k = 0; k < n; ++k) r[k] = opnd((double)x[k], rb);", "for (size_t k = 0; k < n; ++k) r[k] = (double)x[k];"),
+    ("test_oracle_grad.py", C, "for (size_t k = 0; k < n; ++k) r[k] = opnd(x[k], rb);", "for (size_t k = 0; k < n; ++k) r[k] = x[k];"),
+    ("test_oracle_grad.py", C, "z_hidden[(size_t)b * dout + o] = z[o];", "z_hidden[(size_t)b * dout + o] = z[o] - (double)bias[o];"),
+    ("test_oracle_grad.py", C, "z_hidden[(size_t)b * dout + o] = z[o];", "z_hidden[(size_t)b * dout + o] = z[o] > 0.0 ? z[o] : 0.0;"),
+    ("test_oracle_grad.py", C, "if (z_hidden && l + 1 < n_layers) z_hidden += (size_t)B * dout;", "if (z_hidden && l + 1 < n_layers) z_hidden += (size_t)B * din;"),
     # momentum apply + mix
     ("test_oracle_mix.py", C, "const double vn = mu * (double)v[j] + (double)g[j] + wd * (double)x[j];\n            const float vf = (float)vn;           /*",
      "const double vn = mu * (double)v[j] + (double)g[j];\n            const float vf = (float)vn;           /*"),
