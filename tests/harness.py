@@ -54,10 +54,10 @@ def max_abs_err(a: np.ndarray, b: np.ndarray) -> float:
     return float(np.abs(a.astype(np.float64) - b.astype(np.float64)).max()) if a.size else 0.0
 
 
-def compare_on_device(got_dev, want_host: np.ndarray, slab: int = 1 << 20):
+def compare_on_device(got_dev, want_host: np.ndarray, slab: int = 1 << 20, per_row: bool = False):
     """Element-by-element comparison of a device matrix [M, n] with the oracle's host matrix, done with torch on
     the device in double, slab by slab (test arithmetic only).  -> (max over rows of ||got_i - want_i|| / ||want_i||,
-    max |got - want|, max |want|)."""
+    max |got - want|, max |want|); per_row=True gives the per-row ratios as an array instead of their maximum."""
     import torch
     want = torch.from_numpy(want_host).to(got_dev.device)
     assert want.shape == got_dev.shape
@@ -72,5 +72,40 @@ def compare_on_device(got_dev, want_host: np.ndarray, slab: int = 1 << 20):
         den += (b * b).sum(1)
         worst = max(worst, float(d.abs().max()))
         ref = max(ref, float(b.abs().max()))
-    rel = float((num.sqrt() / den.sqrt().clamp_min(1e-30)).max())
-    return rel, worst, ref
+    rel = num.sqrt() / den.sqrt().clamp_min(1e-30)
+    return (rel.cpu().numpy() if per_row else float(rel.max())), worst, ref
+
+
+def relu_disagreements(gpu, Z):
+    """Hidden units whose ReLU decision in the library's last local step (stored activation positive) differs from
+    the sign of the oracle's pre-activation.  Z: list over hidden layers of [M, B, width] (oracle.local_hidden).
+    -> (list over hidden layers of (worker, sample, unit) index arrays, largest |z| among the disputed units
+    relative to its layer's root mean square)."""
+    where, closest = [], 0.0
+    for l, z in enumerate(Z):
+        differ = (gpu.hidden(l + 1).cpu().numpy() > 0) != (z > 0)
+        where.append(np.argwhere(differ))
+        if differ.any():
+            closest = max(closest, float(np.abs(z[differ]).max() / np.sqrt((z * z).mean())))
+    return where, closest
+
+
+def columns_touched_by(dims, ld, disputed):
+    """Boolean mask over a parameter row: the columns whose gradient a disputed ReLU decision changes.  A decision
+    of unit k of hidden layer h (h = 1 ..) switches the back-propagated error of that unit on or off: it changes
+    column k of W_{h-1} and b_{h-1}[k] directly and, through the error handed further down, every parameter of the
+    layers below.  Parameter layout per layer: W row-major [in][out], then b [out]."""
+    mask = np.zeros(ld, dtype=bool)
+    off = [0]
+    for l in range(len(dims) - 1):
+        off.append(off[-1] + dims[l] * dims[l + 1] + dims[l + 1])
+    for h, units in disputed.items():              # h: hidden layer (1-based), units: set of unit indices
+        if not units:
+            continue
+        l = h - 1
+        din, dout = dims[l], dims[l + 1]
+        ks = np.fromiter(units, dtype=np.int64)
+        mask[(off[l] + np.arange(din)[:, None] * dout + ks[None, :]).ravel()] = True
+        mask[off[l] + din * dout + ks] = True
+        mask[:off[l]] = True
+    return mask

@@ -1,0 +1,76 @@
+"""Free runs of the ReLU workloads: where the GPU run and the oracle part ways, and why.
+
+A hidden pre-activation within rounding of zero is positive under one summation order and not under another; the
+ReLU derivative is 1 on one side and 0 on the other, so that worker's gradient jumps (about 1 / sqrt(batch x active
+units) of its norm), and the training dynamics amplify the difference from then on.  These tests run both sides
+freely from the same start, count the disputed ReLU decisions per iteration from the oracle's pre-activations, and
+record the first iteration at which the relative error of the parameters exceeds the tolerance of a T-step run.
+Before the first disputed decision the two runs agree to rounding."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from netmax_inputs import workload
+from harness import inputs_of, make_gpu, make_oracle, compare_on_device, relu_disagreements
+
+pytestmark = pytest.mark.gpu
+
+
+def _free_run(w, steps, tol, operands_bf16=False):
+    """-> (first iteration with a disputed ReLU decision, first iteration whose error exceeds tol, error before the
+    first disputed decision, error after the last step, mean disputed decisions per iteration)."""
+    import oracle
+    oracle.set_threads(16)
+    inp = inputs_of(w)
+    gpu, o = make_gpu(w, inp), make_oracle(w, inp, operands_bf16=operands_bf16)
+    first_flip = first_exceed = None
+    before, rel, total = 0.0, 0.0, 0
+    for it in range(steps):
+        idx = oracle.sample_batch(w.M, w.batch, inp["shard_off"], w.seed, it)
+        Z = oracle.local_hidden(w.dims, o.X, inp["feats"], inp["shard_off"], idx, operands_bf16=operands_bf16)
+        gpu.step(it)
+        assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it)), it
+        where, _ = relu_disagreements(gpu, Z)
+        n = sum(len(d) for d in where)
+        total += n
+        if first_flip is None and n:
+            first_flip = it
+        rel, _, _ = compare_on_device(gpu.get("x"), o.X)
+        if first_flip is None:
+            before = max(before, rel)
+        if first_exceed is None and rel > tol:
+            first_exceed = it
+    oracle.set_threads(1)
+    gpu.close()
+    return first_flip, first_exceed, before, rel, total / steps
+
+
+# (workload, overrides, learning rate, steps run, tolerance, oracle operands, recorded first iteration above the tolerance)
+CASES = [
+    ("cfg2", dict(), 0.01, 400, 1e-4, False, 148),
+    ("cfg2", dict(), 0.05, 60, 1e-4, False, 13),
+    ("cfg5", dict(n_per_worker=64, dims=(48, 32, 16, 10), batch=16), 0.01, 250, 2e-2, False, 84),
+    ("cfg5", dict(n_per_worker=64, dims=(48, 32, 16, 10), batch=16), 0.05, 60, 2e-2, False, 14),
+    ("cfg5", dict(M=8, n_per_worker=512, dims=(3072, 256, 128, 10)), 0.05, 50, 2e-2, False, 14),
+    ("cfg5", dict(n_per_worker=64, dims=(48, 32, 16, 10), batch=16), 0.01, 150, 1e-3, True, 45),
+]
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("name,over,lr,steps,tol,same,recorded", CASES)
+def test_free_run_first_exceeds_the_tolerance_after_a_disputed_relu_decision(name, over, lr, steps, tol, same, recorded):
+    w = replace(workload(name, **over), lr=lr)
+    first_flip, first_exceed, before, final, per_step = _free_run(w, steps, tol, operands_bf16=same)
+    print(f"{name} {over or 'full shape'} lr {lr}, free run against {'the same-operand' if same else 'the exact'} oracle: first "
+          f"disputed ReLU decision at iteration {first_flip}, error before it {before:.1e}, first above {tol:g} at iteration "
+          f"{first_exceed}, {final:.2e} after {steps} iterations, {per_step:.1f} disputed decisions per iteration")
+    assert first_flip is not None and first_exceed is not None
+    if not same and w.gemm_in == "bf16":
+        assert first_flip == 0                     # rounded operands against exact ones: disputed from the start
+    else:
+        # until a decision differs: rounding only (with bf16 operands also activations that the two accumulations
+        # round to different bfloat16 neighbours, 2^-8 of that activation)
+        assert before < (1e-4 if w.gemm_in == "bf16" else 1e-6)
+        assert first_exceed >= first_flip
+    assert recorded / 3 <= first_exceed <= recorded * 3, (first_exceed, recorded)

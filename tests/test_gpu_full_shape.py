@@ -9,7 +9,8 @@ import torch
 
 import paper_2009_05766_amd as nm
 from netmax_inputs import workload, policy_for
-from harness import inputs_of, make_gpu, make_oracle, hyper, rel_err_rows, max_abs_err, compare_on_device
+from harness import (inputs_of, make_gpu, make_oracle, hyper, rel_err_rows, max_abs_err, compare_on_device,
+                     relu_disagreements, columns_touched_by)
 
 pytestmark = pytest.mark.gpu
 
@@ -84,8 +85,15 @@ def test_flat_full_shape_every_element(name):
 def test_cfg5_full_shape_all_workers():
     """cfg5 as the workload list states it (128 workers, 3072-1024-1024-10, batch 128, shards of 4096 images, bf16
     operands): two iterations, each from identical state, all workers.  The gradient against the oracle in the same
-    operand precision (1e-3) and in exact arithmetic (8e-2, see the tolerance notes), the parameters against exact
-    arithmetic (2e-2) and, far tighter, against the same-operand oracle; ReLU decisions counted."""
+    operand precision and in exact arithmetic (8e-2, see the tolerance notes), the parameters against exact
+    arithmetic (2e-2) and, far tighter, against the same-operand oracle.
+
+    ReLU decisions: a hidden pre-activation within rounding of zero is positive under one summation order and not
+    under another (fp32 accumulation on the matrix cores, double in the oracle); the derivative is 1 on one side and
+    0 on the other, which changes that worker's gradient by about 1 / sqrt(batch x active units) of its norm.  The
+    test counts these disagreements from the oracle's pre-activations, requires each to sit at a pre-activation
+    that is zero within rounding, holds workers without any to 1e-3 and allows 2 / sqrt(batch x width / 2) per
+    disagreement for the others."""
     import oracle
     t0 = time.time()
     w = workload("cfg5")
@@ -96,34 +104,41 @@ def test_cfg5_full_shape_all_workers():
     gpu = make_gpu(w, inp)
     same, exact = make_oracle(w, inp, operands_bf16=True), make_oracle(w, inp)
     M, D = w.M, w.D
+    per_flip = 2.0 / np.sqrt(w.batch * min(w.dims[1:-1]) / 2)
     for it in range(2):
         if it > 0:                                     # identical state: the GPU takes over the exact oracle's
             gpu.set("x", exact.X)
             gpu.set("v", exact.V)
             same.X[:], same.V[:] = exact.X, exact.V
+        Xin = exact.X.copy()
         gpu.step(it)
         peers = gpu.peers.cpu().numpy()
         assert np.array_equal(peers, same.step(it)) and np.array_equal(peers, exact.step(it))
         G, X = gpu.get("g"), gpu.get("x")
-        gs_rel, gs_abs, gs_max = compare_on_device(G, same.G)
+        gs_rel, gs_abs, gs_max = compare_on_device(G, same.G, per_row=True)
         ge_rel, ge_abs, _ = compare_on_device(G, exact.G)
         xs_rel, xs_abs, x_max = compare_on_device(X, same.X)
         xe_rel, xe_abs, _ = compare_on_device(X, exact.X)
-        # ReLU decisions of all hidden units of all workers against the same-operand oracle
         idx = oracle.sample_batch(M, w.batch, inp["shard_off"], w.seed, it)
-        Xin = inp["X0"] if it == 0 else Xprev
         Z = oracle.local_hidden(w.dims, Xin, inp["feats"], inp["shard_off"], idx, operands_bf16=True)
-        flips = [int(((gpu.hidden(l + 1).cpu().numpy() > 0) != (Z[l] > 0)).sum()) for l in range(len(Z))]
-        print(f"cfg5 full shape, iteration {it}, all {M} workers: gradient rel {gs_rel:.2e} (same operands) "
-              f"{ge_rel:.2e} (exact); parameters rel {xs_rel:.2e} / {xe_rel:.2e}, max|dx| {xs_abs:.2e} / {xe_abs:.2e} "
-              f"at max|x| {x_max:.2f}; ReLU decisions that differ: {flips} of {[z.size for z in Z]}")
-        assert gs_rel < 1e-3 and ge_rel < 8e-2
+        where, closest = relu_disagreements(gpu, Z)
+        flips = sum(np.bincount(d[:, 0], minlength=M) for d in where)
+        clean = flips == 0
+        print(f"cfg5 full shape, iteration {it}, all {M} workers: gradient rel {gs_rel[clean].max():.2e} (same operands, "
+              f"{int(clean.sum())} workers whose ReLU decisions all agree) {gs_rel.max():.2e} (all; {int(flips.sum())} of "
+              f"{sum(z.size for z in Z)} decisions differ, at |z| <= {closest:.1e} of the layer's rms) {ge_rel:.2e} (exact); "
+              f"parameters rel {xs_rel:.2e} / {xe_rel:.2e}, max|dx| {xs_abs:.2e} / {xe_abs:.2e} at max|x| {x_max:.2f}")
+        # how far from zero a disputed pre-activation can be: one input activation that the two accumulations round
+        # to different bfloat16 neighbours moves z by 2^-8 of that term, which can be as large as z's usual size
+        assert flips.sum() <= 1e-5 * sum(z.size for z in Z) and closest < 2.0 ** -8
+        assert gs_rel[clean].max() < 1e-3
+        assert np.all(gs_rel <= 1e-3 + per_flip * flips)
+        assert ge_rel < 8e-2
         assert xs_rel < TOL_STEP and xe_rel < TOL_BF16
         # element by element: alpha times the gradient's deviation, plus the update's own roundings
         assert xs_abs <= h["lr"] * gs_abs + 4 * EPS * x_max
         assert xe_abs <= h["lr"] * ge_abs + 4 * EPS * x_max
         assert not X[:, D:].any()
-        Xprev = exact.X.copy()
     cd = gpu.consensus_dist()
     assert cd == pytest.approx(exact.consensus_dist(), rel=1e-3)
     oracle.set_threads(1)
@@ -134,27 +149,57 @@ def test_cfg5_full_shape_all_workers():
 @pytest.mark.timeout(600)
 def test_cfg2_full_shape_full_T_in_windows():
     """cfg2 at full shape over its whole horizon T = 1000: windows of 20 iterations, the GPU run re-synchronised from
-    the oracle's state at the start of each; row norm and element-wise bound at the end of every window."""
+    the oracle's state at the start of each.  At the end of every window: the row norm at 1e-4, and element by
+    element the same tolerance in the maximum norm for every column that no disputed ReLU decision of the window
+    touches; the touched columns (the weights into a disputed hidden unit and its bias) get the bound that follows
+    from the size of one switched-off error term.  The disputed decisions are counted from the oracle's
+    pre-activations, each must sit at a pre-activation that is zero within the drift of the window."""
     import oracle
     t0 = time.time()
     w = workload("cfg2")
     inp = inputs_of(w)
+    h = hyper(w, inp["rho"])
     oracle.set_threads(16)
     gpu, o = make_gpu(w, inp), make_oracle(w, inp)
-    K, worst_rel, worst_abs = 20, 0.0, 0.0
+    K, worst_rel, worst_clean, worst_touched, n_flips, windows_with = 20, 0.0, 0.0, 0.0, 0, 0
+    d_in, d_hidden = w.dims[0], w.dims[1]
+    feat_max = float(np.abs(inp["feats"]).max())
+    disputed, count = {1: set()}, 0
     for it in range(w.T):
         if it % K == 0:
             gpu.set("x", o.X)
             gpu.set("v", o.V)
+            disputed, count = {1: set()}, 0
+        idx = oracle.sample_batch(w.M, w.batch, inp["shard_off"], w.seed, it)
+        Z = oracle.local_hidden(w.dims, o.X, inp["feats"], inp["shard_off"], idx)
         gpu.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it)), it
+        where, closest = relu_disagreements(gpu, Z)
+        # from identical state only summation order separates the two sides; later in a window the drift a first
+        # dispute caused (about 1e-3 of the unit's pre-activation) can dispute further decisions of that unit
+        assert closest < (1e-5 if it % K == 0 else 1e-2), (it, closest)
+        disputed[1] |= set(where[0][:, 2].tolist())
+        count += len(where[0])
         if (it + 1) % K == 0:
             X = gpu.get("x").cpu().numpy()
-            rel, err = rel_err_rows(X, o.X), max_abs_err(X, o.X)
-            worst_rel, worst_abs = max(worst_rel, rel), max(worst_abs, err / np.abs(o.X).max())
+            rel = rel_err_rows(X, o.X)
+            x_max = float(np.abs(o.X).max())
+            touched = columns_touched_by(w.dims, w.ld, disputed)
+            err = np.abs(X.astype(np.float64) - o.X).max(axis=0)
+            clean_err = float(err[~touched].max()) / x_max
+            touched_err = float(err[touched].max()) / x_max if count else 0.0
+            # one switched error term: |dz| sums to at most 2 / batch per sample, times the next layer's largest
+            # weight, times the largest input; momentum sums it to 1 / (1 - mu), the step size scales it
+            w_next = float(np.abs(o.X[:, w.D - w.dims[-1] - d_hidden * w.dims[-1]:w.D - w.dims[-1]]).max())
+            per_flip = h["lr"] / (1 - h["momentum"]) * (2.0 / w.batch) * w_next * max(1.0, feat_max)
             assert rel < TOL_RUN, (it, rel)
-            assert err <= TOL_RUN * np.abs(o.X).max(), (it, err)      # the same tolerance in the maximum norm
-    print(f"cfg2 full shape, {w.T} iterations in windows of {K}: worst rel {worst_rel:.2e}, worst max|dx|/max|x| "
-          f"{worst_abs:.2e}; {time.time() - t0:.0f} s")
+            assert clean_err <= TOL_RUN, (it, clean_err)
+            assert touched_err * x_max <= TOL_RUN * x_max + 2 * count * per_flip, (it, touched_err, count)
+            worst_rel, worst_clean, worst_touched = max(worst_rel, rel), max(worst_clean, clean_err), max(worst_touched, touched_err)
+            n_flips += count
+            windows_with += count > 0
+    print(f"cfg2 full shape, {w.T} iterations in windows of {K}: worst rel {worst_rel:.2e}; max|dx|/max|x| {worst_clean:.2e} "
+          f"outside the columns of disputed units, {worst_touched:.2e} inside; {n_flips} disputed ReLU decisions in "
+          f"{windows_with} of {w.T // K} windows; {time.time() - t0:.0f} s")
     oracle.set_threads(1)
     gpu.close()

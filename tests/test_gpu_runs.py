@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from netmax_inputs import workload
-from harness import inputs_of, make_gpu, make_oracle, rel_err_rows
+from harness import inputs_of, make_gpu, make_oracle, rel_err_rows, max_abs_err, relu_disagreements, columns_touched_by
 
 pytestmark = pytest.mark.gpu
 
@@ -19,6 +19,48 @@ def _sync_gpu_from_oracle(gpu, o):
     gpu.set("v", o.V)
 
 
+def _has_relu(w):
+    return len(w.dims) > 2
+
+
+class _Disputes:
+    """Tracks, for ReLU networks, which hidden units had a ReLU decision on which the library and the oracle differ
+    (counted from the oracle's pre-activations), so that the element-wise bound can leave out exactly the columns
+    such a decision touches.  Nothing to track for flat models and softmax regression."""
+
+    def __init__(self, w, inp, operands_bf16=False):
+        self.w, self.inp, self.bf16 = w, inp, operands_bf16
+        self.reset()
+
+    def reset(self):
+        self.units = {h: set() for h in range(1, len(self.w.dims) - 1)}
+
+    def before_step(self, o, it):
+        import oracle
+        if _has_relu(self.w):
+            idx = oracle.sample_batch(self.w.M, self.w.batch, self.inp["shard_off"], self.w.seed, it)
+            self.Z = oracle.local_hidden(self.w.dims, o.X, self.inp["feats"], self.inp["shard_off"], idx,
+                                         operands_bf16=self.bf16)
+
+    def after_step(self, gpu):
+        if _has_relu(self.w):
+            where, _ = relu_disagreements(gpu, self.Z)
+            for h, d in enumerate(where, start=1):
+                self.units[h] |= set(d[:, 2].tolist())
+
+    def check(self, X, o, tol, what):
+        """Row norm, and the same tolerance in the maximum norm element by element (outside the columns a disputed
+        ReLU decision touches).  -> the row-norm error."""
+        rel = rel_err_rows(X, o.X)
+        assert rel < tol, (what, rel)
+        err = np.abs(X.astype(np.float64) - o.X).max(axis=0)
+        if any(self.units.values()):
+            err = err[~columns_touched_by(self.w.dims, self.w.ld, self.units)]
+        if err.size:
+            assert err.max() <= tol * np.abs(o.X).max(), (what, float(err.max()))
+        return rel
+
+
 def _free_run(w, T, ora_threads=8, cd_rel=1e-3):
     import oracle
     oracle.set_threads(ora_threads)
@@ -26,13 +68,14 @@ def _free_run(w, T, ora_threads=8, cd_rel=1e-3):
     gpu, o = make_gpu(w, inp), make_oracle(w, inp)
     cd0 = gpu.consensus_dist()
     assert cd0 == pytest.approx(o.consensus_dist(), rel=1e-6)
-    worst = 0.0
     for it in range(T):
         gpu.step(it)
         peer = o.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), peer)
     X = gpu.get("x").cpu().numpy()
     err = rel_err_rows(X, o.X)
+    if not _has_relu(w):                         # the T-step tolerance element by element, in the maximum norm
+        assert max_abs_err(X, o.X) <= TOL_RUN * np.abs(o.X).max()
     cd = gpu.consensus_dist()
     assert cd == pytest.approx(o.consensus_dist(), rel=cd_rel)
     assert np.all(X[:, w.D:] == 0)
@@ -46,14 +89,17 @@ def _stepwise(w, T, tol, ora_threads=8):
     oracle.set_threads(ora_threads)
     inp = inputs_of(w)
     gpu, o = make_gpu(w, inp), make_oracle(w, inp)
+    disputes = _Disputes(w, inp)
     worst = 0.0
     for it in range(T):
         _sync_gpu_from_oracle(gpu, o)
+        disputes.reset()
+        disputes.before_step(o, it)
         gpu.step(it)
         peer = o.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), peer)
-        worst = max(worst, rel_err_rows(gpu.get("x").cpu().numpy(), o.X))
-        assert worst < tol, (it, worst)
+        disputes.after_step(gpu)
+        worst = max(worst, disputes.check(gpu.get("x").cpu().numpy(), o, tol, it))
     oracle.set_threads(1)
     gpu.close()
     return worst
@@ -69,17 +115,19 @@ def _windows(w, T, K, tol, ora_threads=8, operands_bf16=False):
     oracle.set_threads(ora_threads)
     inp = inputs_of(w)
     gpu, o = make_gpu(w, inp), make_oracle(w, inp, operands_bf16=operands_bf16)
+    disputes = _Disputes(w, inp, operands_bf16)
     worst = 0.0
     for it in range(T):
         if it % K == 0:
             _sync_gpu_from_oracle(gpu, o)
+            disputes.reset()
+        disputes.before_step(o, it)
         gpu.step(it)
         peer = o.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), peer)
+        disputes.after_step(gpu)
         if (it + 1) % K == 0 or it + 1 == T:
-            e = rel_err_rows(gpu.get("x").cpu().numpy(), o.X)
-            worst = max(worst, e)
-            assert e < tol, (it, e)
+            worst = max(worst, disputes.check(gpu.get("x").cpu().numpy(), o, tol, it))
     oracle.set_threads(1)
     gpu.close()
     return worst
@@ -93,10 +141,10 @@ def test_cfg1_full_run():
     assert cd < cd0
 
 
-def test_cfg2_full_shape():
+def test_cfg2_full_shape_per_step():
+    """Ten iterations, each from identical state (the whole horizon in windows: test_gpu_full_shape.py)."""
     w = workload("cfg2")
     assert _stepwise(w, 10, TOL_STEP) < TOL_STEP
-    assert _windows(w, 120, 20, TOL_RUN) < TOL_RUN
 
 
 def test_cfg2_reduced_shape_full_T():
@@ -143,51 +191,15 @@ def test_cfg5_all_workers_tiny_layers_full_T():
     assert err < 0.1, err           # sanity only: operand rounding plus ReLU kinks over 500 free steps
 
 
-def test_cfg5_full_shape_sampled_workers():
-    """cfg5 at its full layer widths, batch and worker count, in the launch configuration of the
-    benchmark (shards shortened to 256 images to keep host data generation short).  The oracle
-    recomputes the gradient and the update of a few sampled workers and their peers' rows."""
-    import oracle
-    from harness import hyper
-    w = workload("cfg5", n_per_worker=256)
-    inp = inputs_of(w)
-    h = hyper(w, inp["rho"])
-    gpu = make_gpu(w, inp)
-    oracle.set_threads(8)
-    T, last = oracle.thresholds(inp["P"])
-    wtab = oracle.mix_weights(inp["P"], None, h["lr"], h["rho"])
-    gpu.step(0)
-    peers = oracle.sample_peers(T, last, w.seed, 0)
-    assert np.array_equal(gpu.peers.cpu().numpy(), peers)
-    idx = oracle.sample_batch(w.M, w.batch, inp["shard_off"], w.seed, 0)
-    G, X1 = gpu.get("g").cpu().numpy(), gpu.get("x").cpu().numpy()
-    for i in (0, 37, 127):
-        s, e = inp["shard_off"][i], inp["shard_off"][i + 1]
-        for same, tol in ((True, 1e-3), (False, 8e-2)):
-            g, _ = oracle.grad_mlp(w.dims, inp["X0"][i], inp["feats"][s:e], inp["labels"][s:e], idx[i],
-                                   operands_bf16=same)
-            assert rel_err_rows(G[i:i + 1, :w.D], g[None, :]) < tol
-        # the update of worker i from the oracle's exact-arithmetic gradient and its peer's row
-        m = int(peers[i])
-        sub = np.stack([inp["X0"][i], inp["X0"][m]])
-        gsub = np.zeros_like(sub)
-        gsub[0, :w.D] = g
-        vsub = np.zeros_like(sub)
-        wpair = np.zeros((2, 2))
-        wpair[0, 1] = wtab[i, m]
-        out = oracle.mix(sub, gsub, vsub, np.array([1, 1], np.int32), wpair, h["lr"], h["momentum"], h["weight_decay"])
-        assert rel_err_rows(X1[i:i + 1], out[0:1]) < 1e-4     # far inside the bf16 tolerance: only alpha * g carries its noise
-    oracle.set_threads(1)
-    gpu.close()
-
-
 @pytest.mark.parametrize("name", ["cfg3", "cfg4"])
-def test_flat_full_shape_sampled_columns(name):
-    """Full-size run in the benchmark's launch configuration.  The update is separable by column, so
-    the oracle recomputes windows of columns (start, chunk boundaries, ragged end) for all workers."""
+def test_flat_full_shape_full_T_sampled_columns(name):
+    """Full-size free run over the whole horizon T = 200 in the benchmark's launch configuration.  The update is
+    separable by column, so the oracle follows windows of columns (start, tile and chunk boundaries, ragged end) of
+    all workers for all 200 iterations; every element of x and v against the run tolerance.  (All columns for a
+    short horizon: test_gpu_full_shape.py.)"""
     import oracle
     w = workload(name)
-    T = 4
+    T = w.T
     P, rho = __import__("netmax_inputs").policy_for(w)
     M, ld = w.M, w.ld
     import paper_2009_05766_amd as nm
@@ -213,22 +225,22 @@ def test_flat_full_shape_sampled_columns(name):
         valid = min(width, w.D - c0)
         oracles.append(oracle.Oracle(M=M, ld=width, D=valid, dims=(), batch=0, seed=w.seed, P=P, X0=x0, col0=c0,
                                      **hyper(w, rho)))
+    peers = torch.empty((T, M), dtype=torch.int32, device="cuda")
     for it in range(T):
         gpu.step(it)
-        peers = gpu.peers.cpu().numpy()
+        peers[it] = gpu.peers
+    peers = peers.cpu().numpy()
+    for it in range(T):
         for o in oracles:
-            assert np.array_equal(o.step(it), peers)
+            assert np.array_equal(o.step(it), peers[it])
+    worst = 0.0
     for c0, o in zip(windows, oracles):
-        got = gpu.get_window("x", c0, width).cpu().numpy()
-        assert rel_err_rows(got, o.X) < TOL_STEP * T
-        assert rel_err_rows(gpu.get_window("v", c0, width).cpu().numpy(), o.V) < TOL_STEP * T
-    X = gpu.get("x")
-    # consensus distance at full size against torch on the device, in double
-    want = 0.0
-    for c in range(0, ld, 1 << 20):                       # in slabs, to bound the fp64 temporaries
-        Xd = X[:, c:c + (1 << 20)].double()
-        want += float(((Xd - Xd.mean(0, keepdim=True)) ** 2).sum())
-    assert gpu.consensus_dist() == pytest.approx(want, rel=1e-9)
+        for what, want in (("x", o.X), ("v", o.V)):
+            got = gpu.get_window(what, c0, width).cpu().numpy()
+            assert rel_err_rows(got, want) < TOL_RUN
+            assert max_abs_err(got, want) <= TOL_RUN * np.abs(want).max()
+            worst = max(worst, max_abs_err(got, want) / np.abs(want).max())
+    print(f"{name} full shape, free run of {T} iterations, {len(windows)} windows of {width} columns: worst max|d|/max {worst:.2e}")
     gpu.close()
 
 
