@@ -97,36 +97,16 @@ def cpu_baseline(w, inp, budget_s: float = 12.0):
             "all_threads": {"value": w.M / (dt_mt * scale), "cores": threads, "iterations": iters_mt}}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", help="cfg1..cfg5 (default: cfg3, the HBM-bound ResNet18-sized mix)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", choices=("calls", "run", "graph"), default="calls",
-                    help="calls: the three entry points per step, events around each phase (default); run: one "
-                         "netmax_run call for all steps; graph: netmax_run replaying captured HIP graphs")
-    ap.add_argument("--fuse", action="store_true",
-                    help="with --mode run or graph, perceptron workloads on the matrix-core kernels: apply the update "
-                         "inside the weight-gradient kernels (netmax_set_fusion)")
-    ap.add_argument("--copy-probe", type=int, default=0,
-                    help="before the timed region, run this many plain device copies of the parameter matrix "
-                         "(a kernel of known traffic, used to scale profiler byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: the library runs on one GPU only (no collectives, nothing sharded); use --gpus 1", file=sys.stderr)
-        return 2
-
+def measure(w, steps, warmup, mode, fuse, copy_probe):
+    """One workload: inputs to HBM, warm-up, then `steps` timed iterations.  -> (result dict, inputs)."""
     import numpy as np
     import torch
     import paper_2009_05766_amd as nm
-    from netmax_inputs import workload, policy_for, make_shards, init_params, hyperparameters as hyper
+    from netmax_inputs import policy_for, make_shards, init_params, hyperparameters as hyper
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    w = workload(args.workload)
+    if fuse and mode == "calls":
+        print("bench.py: --fuse needs --mode run or --mode graph (the three separate entry points are never fused)", file=sys.stderr)
+        return None, None
     t_in = time.perf_counter()
     P, rho = policy_for(w)
     feats, labels, shard_off = make_shards(w)
@@ -142,21 +122,21 @@ def main() -> int:
     torch.cuda.synchronize()
     cd0 = gpu.consensus_dist()
 
-    for it in range(args.warmup):
+    for it in range(warmup):
         gpu.step(it)
     torch.cuda.synchronize()
 
-    for _ in range(args.copy_probe):
+    for _ in range(copy_probe):
         gpu.x_b.copy_(gpu.x_a) if gpu.params() is gpu.x_a else gpu.x_a.copy_(gpu.x_b)
     torch.cuda.synchronize()
 
-    K = args.steps
-    K_ev = K if args.mode == "calls" else min(K, 50)      # phase timing: events around every entry point
+    K = steps
+    K_ev = K if mode == "calls" else min(K, 50)      # phase timing: events around every entry point
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K_ev)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(K_ev):
-        it = args.warmup + k
+        it = warmup + k
         e = ev[k]
         e[0].record()
         nm.netmax_sample_peers(gpu.ctx, it, gpu.peers)
@@ -167,17 +147,14 @@ def main() -> int:
         e[3].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    if args.fuse and args.mode == "calls":
-        print("bench.py: --fuse needs --mode run or --mode graph (the three separate entry points are never fused)", file=sys.stderr)
-        return 2
-    if args.mode != "calls":
-        if args.fuse:
+    if mode != "calls":
+        if fuse:
             nm.netmax_set_fusion(gpu.ctx, True)
-        first = args.warmup + K_ev
-        gpu.run(first, 4, use_graph=args.mode == "graph")          # captures both directions outside the timed region
+        first = warmup + K_ev
+        gpu.run(first, 4, use_graph=mode == "graph")          # captures both directions outside the timed region
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        gpu.run(first + 4, K, use_graph=args.mode == "graph")
+        gpu.run(first + 4, K, use_graph=mode == "graph")
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
 
@@ -198,15 +175,68 @@ def main() -> int:
                 "achieved_counting_peer_read": MIX_BYTES_NAIVE * elems / mix_s / 1e9}
 
     out = {"metric": "worker-iterations/sec (sample+grad+mix)", "value": value, "unit": "worker-iterations/s",
-           "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+           "n_gpus": 1, "steps": K, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.gemm_in == "bf16" else "f32",
            "data": "synthetic", "config": {"workload": describe(w), "M": w.M, "D": w.D, "iterations": K,
-                                           "launch": args.mode + ("+fused" if args.fuse else "")},
+                                           "launch": mode + ("+fused" if fuse else "")},
            "phase_ms": {"sample_peers": float(ms_sample), "local_step": float(ms_grad), "mix": float(ms_mix)},
            "consensus_distance": {"before": cd0, "after": cd1},
            "roofline": roofline}
     gpu.close()
     del gpu
+    torch.cuda.set_stream(torch.cuda.default_stream())
+    torch.cuda.empty_cache()
+    return out, inp
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3", help="cfg1..cfg5 (default: cfg3, the HBM-bound ResNet18-sized mix)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the short measurements of the other four workloads (key per_config)")
+    ap.add_argument("--mode", choices=("calls", "run", "graph"), default="calls",
+                    help="calls: the three entry points per step, events around each phase (default); run: one "
+                         "netmax_run call for all steps; graph: netmax_run replaying captured HIP graphs")
+    ap.add_argument("--fuse", action="store_true",
+                    help="with --mode run or graph, perceptron workloads on the matrix-core kernels: apply the update "
+                         "inside the weight-gradient kernels (netmax_set_fusion)")
+    ap.add_argument("--copy-probe", type=int, default=0,
+                    help="before the timed region, run this many plain device copies of the parameter matrix "
+                         "(a kernel of known traffic, used to scale profiler byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: the library runs on one GPU only (no collectives, nothing sharded); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from netmax_inputs import workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    w = workload(args.workload)
+    out, inp = measure(w, args.steps, args.warmup, args.mode, args.fuse, args.copy_probe)
+    if out is None:
+        return 2
+    if not args.no_per_config:
+        # the other four workloads in the same process: fewer steps, all steps enqueued by one netmax_run call (the
+        # phase split from a separate pass with events around each entry point); no CPU baseline for them
+        per = {}
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+            if name == w.name:
+                continue
+            small = name in ("cfg1", "cfg2")
+            o, _ = measure(workload(name), 400 if small else 40, 20 if small else 5, "run", False, 0)
+            per[name] = {"workload": o["config"]["workload"], "value": o["value"], "unit": o["unit"], "steps": o["steps"],
+                         "us_per_step": o["ms_per_step"] * 1e3,
+                         "phase_us": {k: v * 1e3 for k, v in o["phase_ms"].items()},
+                         "mix_roofline_frac": o["roofline"]["frac"], "mix_achieved_GBs": o["roofline"]["achieved"],
+                         "dtype": o["dtype"], "launch": o["config"]["launch"]}
+        out["per_config"] = per
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out), flush=True)
