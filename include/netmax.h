@@ -51,7 +51,7 @@ typedef struct netmax_ctx netmax_ctx; /* opaque, library-owned */
 typedef enum {
     NETMAX_OK = 0,
     NETMAX_EINVAL = 1,      /* null pointer, M < 2, bad shape, bad alignment, invalid row of P */
-    NETMAX_EINFEASIBLE = 2, /* a selectable pair has mix weight >= 1 (strict mode: >= 1/2, i.e. violates (o3)) */
+    NETMAX_EINFEASIBLE = 2, /* a selectable pair has mix weight >= 1 (strict mode: > 1/2, i.e. violates (o3)) */
     NETMAX_ESTATE = 3,      /* state or data not bound, or call does not fit the model kind */
     NETMAX_EDEVICE = 4,     /* a HIP call failed */
     NETMAX_ENOMEM = 5
@@ -81,7 +81,9 @@ typedef struct {
     float rho;         /* consensus weight of Eq. (1) */
     float grad_sigma;  /* FLAT only */
     uint64_t seed;
-    int32_t strict_o3; /* nonzero: require w < 1/2 for every selectable pair (constraint (o3)) */
+    int32_t strict_o3; /* nonzero: require w <= 1/2 for every selectable pair: constraint (o3) taken with >=, as
+                          netmax_generate_policy takes it (links on the bound have w = 1/2); a relative 1e-6 is
+                          allowed for a rho that was rounded to single precision */
     const double *P;   /* host, M*M row-major; p_im = probability that worker i selects m (Section II-B) */
     const uint8_t *adj;/* host, M*M neighbourhood indicators d_im, or NULL = complete graph without self loops */
     void *stream;      /* hipStream_t, NULL = the null stream */
@@ -189,6 +191,9 @@ int netmax_set_fusion(netmax_ctx *ctx, int32_t on);
  *
  * netmax_activity: host helper, p_act_out[i] = p_i from iteration times t (host double [M][M], diagonal ignored),
  * policy P (host double [M][M]) and adj (host, may be NULL).  NETMAX_EINVAL if a worker's mean time is not positive.
+ * netmax_mean_times: host helper, tbar_out[i] = tbar_i of Eq. (d3) (host double [M]) and, if rate_out is not NULL,
+ * sum_i 1 / tbar_i, the number of global steps per unit of time (the normaliser of Eq. (d4)).  Same arguments and
+ * error as netmax_activity.
  * netmax_set_activity: installs p_act (host double [M], non-negative, sum 1 within 1e-9) as 32-bit cumulative
  * thresholds, as for a policy row.
  * netmax_async_run: global steps first_step .. first_step + n_steps - 1 on the context's stream.  Step k draws i_k
@@ -199,6 +204,8 @@ int netmax_set_fusion(netmax_ctx *ctx, int32_t on);
  * used).  Needs netmax_bind_state, netmax_set_activity and, for perceptron models, netmax_bind_data
  * (else NETMAX_ESTATE).  Returns after enqueueing. */
 int netmax_activity(int32_t M, const double *t_host, const double *P_host, const uint8_t *adj, double *p_act_out);
+int netmax_mean_times(int32_t M, const double *t_host, const double *P_host, const uint8_t *adj, double *tbar_out,
+                      double *rate_out);
 int netmax_set_activity(netmax_ctx *ctx, const double *p_act);
 int netmax_async_run(netmax_ctx *ctx, uint64_t first_step, uint64_t n_steps, int32_t *active_dev, int32_t *peers_dev);
 

@@ -24,7 +24,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_update_times_async", "netmax_activity", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_update_times_async", "netmax_activity", "netmax_mean_times", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
     "netmax_consensus_dist", "netmax_consensus_dist_static", "netmax_params", "netmax_losses", "netmax_read_losses", "netmax_read_hidden", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -84,6 +84,7 @@ def load():
         "netmax_update_times_async": (C.c_int, [vp, vp, vp, C.c_uint64, vp, f32, vp, vp]),
         "netmax_set_fusion": (C.c_int, [vp, i32]),
         "netmax_activity": (C.c_int, [C.c_int32, vp, vp, vp, vp]),
+        "netmax_mean_times": (C.c_int, [C.c_int32, vp, vp, vp, vp, C.POINTER(C.c_double)]),
         "netmax_set_activity": (C.c_int, [vp, vp]),
         "netmax_async_run": (C.c_int, [vp, C.c_uint64, C.c_uint64, vp, vp]),
         "netmax_consensus_dist": (C.c_int, [vp, C.POINTER(C.c_double)]),
@@ -252,6 +253,18 @@ def netmax_activity(t: np.ndarray, P: np.ndarray, adj: Optional[np.ndarray] = No
     if rc != NETMAX_OK:
         raise NetmaxError(rc, "a worker's mean iteration time is not positive")
     return out
+
+
+def netmax_mean_times(t: np.ndarray, P: np.ndarray, adj: Optional[np.ndarray] = None):
+    """-> (tbar float64 [M] of Eq. (d3), global steps per unit of time = sum_i 1 / tbar_i)."""
+    t, P, adj = _host(t, np.float64), _host(P, np.float64), _host(adj, np.uint8)
+    M = P.shape[0]
+    tbar = np.empty(M, np.float64)
+    rate = C.c_double()
+    rc = load().netmax_mean_times(M, _hp(t), _hp(P), _hp(adj), _hp(tbar), C.byref(rate))
+    if rc != NETMAX_OK:
+        raise NetmaxError(rc, "a worker's mean iteration time is not positive")
+    return tbar, rate.value
 
 
 def netmax_set_activity(ctx, p_act: np.ndarray):

@@ -95,7 +95,10 @@ static int build_tables(int M, const double *P, const uint8_t *adj, double alpha
     thr.assign((size_t)M * M, 0u);
     last.assign(M, 0);
     w.assign((size_t)M * M, 0.0f);
-    const double limit = (strict && mix_mode == NETMAX_MIX_POLICY) ? 0.5 : 1.0;   // (o3) concerns Algorithm 2's weights
+    // (o3) concerns Algorithm 2's weights.  Strict mode takes it with >=, as the policy generator does (links that
+    // end on the bound get w = 1/2 exactly), with room for a rho that went through single precision.
+    const bool strict_policy = strict && mix_mode == NETMAX_MIX_POLICY;
+    const double limit = strict_policy ? 0.5 * (1.0 + 1e-6) : 1.0;
     char buf[200];
     for (int i = 0; i < M; ++i) {
         const double *row = P + (size_t)i * M;
@@ -138,9 +141,9 @@ static int build_tables(int M, const double *P, const uint8_t *adj, double alpha
             if (m != i && row[m] > 0.0) {
                 const double links = adj ? (double)((adj[(size_t)i * M + m] != 0) + (adj[(size_t)m * M + i] != 0)) : 2.0;
                 const double weight = mix_mode == NETMAX_MIX_FIXED ? fixed_weight : alpha * rho * links / (2.0 * row[m]);
-                if (!(weight < limit)) {
-                    snprintf(buf, sizeof buf, "mix weight of pair (%d,%d) is %g, must be below %g%s", i, m, weight, limit,
-                             strict ? " (constraint (o3))" : "");
+                if (strict_policy ? !(weight <= limit) : !(weight < limit)) {
+                    snprintf(buf, sizeof buf, "mix weight of pair (%d,%d) is %g, must be %s %g%s", i, m, weight,
+                             strict_policy ? "at most" : "below", strict_policy ? 0.5 : 1.0, strict ? " (constraint (o3))" : "");
                     why = buf;
                     return NETMAX_EINFEASIBLE;
                 }
@@ -702,6 +705,23 @@ extern "C" int netmax_activity(int32_t M, const double *t_host, const double *P_
         total += p_act_out[i];
     }
     for (int i = 0; i < M; ++i) p_act_out[i] /= total;       // Eq. (d4)
+    return NETMAX_OK;
+}
+
+extern "C" int netmax_mean_times(int32_t M, const double *t_host, const double *P_host, const uint8_t *adj, double *tbar_out,
+                                 double *rate_out)
+{
+    if (M < 1 || !t_host || !P_host || !tbar_out) return NETMAX_EINVAL;
+    double rate = 0.0;
+    for (int i = 0; i < M; ++i) {
+        double tbar = 0.0;                                   // Eq. (d3); d_ii = 0
+        for (int m = 0; m < M; ++m)
+            if (m != i && (!adj || adj[(size_t)i * M + m])) tbar += t_host[(size_t)i * M + m] * P_host[(size_t)i * M + m];
+        if (!(tbar > 0.0) || !std::isfinite(tbar)) return NETMAX_EINVAL;
+        tbar_out[i] = tbar;
+        rate += 1.0 / tbar;                                  // the normaliser of Eq. (d4)
+    }
+    if (rate_out) *rate_out = rate;
     return NETMAX_OK;
 }
 

@@ -30,9 +30,7 @@ def run_policy(w, inp, P, rho, t, budget, chunk=200):
                     X0=inp["X0"], feats=inp["feats"], labels=inp["labels"], shard_off=inp["shard_off"], **h)
     p_act = nm.netmax_activity(t, P)
     nm.netmax_set_activity(gpu.ctx, p_act)
-    off = ~np.eye(w.M, dtype=bool)
-    tbar = (t * P * off).sum(axis=1)                       # Eq. (d3)
-    rate = float((1.0 / tbar).sum())                       # global steps per unit of simulated time
+    tbar, rate = nm.netmax_mean_times(t, P)                # Eq. (d3); global steps per unit of simulated time
     steps = int(budget * rate)
     active = torch.zeros(chunk, dtype=torch.int32, device=gpu.device)
     peers = torch.zeros(chunk, dtype=torch.int32, device=gpu.device)
@@ -64,13 +62,12 @@ def run_dynamic(w, inp, P, rho, networks, segment_time, adaptive, K, R, periods=
     mon = Monitor(gpu, alpha=h["lr"], K=K, R=R, beta=beta, initial_times=networks[0])
     active = torch.zeros(chunk, dtype=torch.int32, device=gpu.device)
     peers = torch.zeros(chunk, dtype=torch.int32, device=gpu.device)
-    off = ~np.eye(w.M, dtype=bool)
     done, policies = 0, 0
     for t in networks:
         mon.set_network(t)
         for _ in range(periods):                                         # the monitor's schedule period T_s
             nm.netmax_set_activity(gpu.ctx, nm.netmax_activity(t, P))
-            rate = float((1.0 / (t * P * off).sum(axis=1)).sum())
+            _, rate = nm.netmax_mean_times(t, P)
             left = int(segment_time / periods * rate)
             while left > 0:
                 n = min(chunk, left)

@@ -68,6 +68,10 @@ def test_host_table_errors():
         nm.netmax_build_tables(P2, None, 0.1, 0.006, strict_o3=True)
     assert e.value.code == nm.NETMAX_EINFEASIBLE
     nm.netmax_build_tables(P2, None, 0.1, 0.006, strict_o3=False)
+    nm.netmax_build_tables(P2, None, 0.1, 0.005, strict_o3=True)      # w = 1/2 exactly: on the bound of (o3), accepted
+    with pytest.raises(nm.NetmaxError) as e:
+        nm.netmax_build_tables(P2, None, 0.1, 0.005 * (1 + 1e-5), strict_o3=True)
+    assert e.value.code == nm.NETMAX_EINFEASIBLE
     adj = np.ones((3, 3), np.uint8) - np.eye(3, dtype=np.uint8)
     adj[0, 2] = adj[2, 0] = 0
     with pytest.raises(nm.NetmaxError) as e:     # positive probability on a non-edge, constraint (o4)
@@ -85,3 +89,17 @@ def test_host_tables_fixed_weight_mode(ora):
     assert np.array_equal(wt, ora.mix_weights_fixed(P, 0.5).astype(np.float32))
     with pytest.raises(nm.NetmaxError):
         nm.netmax_build_tables(P, None, 0.01, rho, mix_mode=nm.NETMAX_MIX_FIXED, fixed_weight=1.0)
+
+
+def test_mean_iteration_times_and_step_rate(ora):
+    """Eq. (d3) and the normaliser of Eq. (d4): consistent with the activity probabilities of the oracle."""
+    from netmax_inputs import iteration_times
+    for name in ("cfg1", "cfg4"):
+        w = workload(name)
+        P, _ = policy_for(w)
+        t = iteration_times(w.links, w.M)
+        tbar, rate = nm.netmax_mean_times(t, P)
+        np.testing.assert_allclose((1.0 / tbar) / rate, ora.activity(t, P), rtol=1e-13)
+        np.testing.assert_allclose(nm.netmax_activity(t, P), ora.activity(t, P), rtol=1e-13)
+        # one row by hand: sum over the other workers of t_im p_im
+        assert tbar[2] == pytest.approx(sum(t[2, m] * P[2, m] for m in range(w.M) if m != 2), rel=1e-14)

@@ -47,7 +47,9 @@ def test_generated_policy_matches_oracle(recipe, M, adj, alpha, K, R):
     np.testing.assert_allclose(got["P"], want["P"], rtol=0, atol=1e-9)
     # and the result can drive the iteration: rows are distributions and the weights satisfy (o3)
     np.testing.assert_allclose(got["P"].sum(1), 1.0, atol=1e-12)
-    thr, last, w = nm.netmax_build_tables(got["P"], A, alpha, got["rho"], strict_o3=False)
+    # strict mode accepts the library's own policy, also with rho rounded to single precision (as netmax_set_policy
+    # receives it): links that end on the bound of (o3) have weight 1/2
+    thr, last, w = nm.netmax_build_tables(got["P"], A, alpha, float(np.float32(got["rho"])), strict_o3=True)
     assert w.max() <= 0.5 * (1 + 1e-6)
 
 
@@ -103,3 +105,29 @@ def test_activity_matches_oracle():
         assert np.allclose(nm.netmax_activity(t, P2, adj), oracle.activity(t, P2, adj), rtol=1e-13)
     with pytest.raises(nm.NetmaxError):
         nm.netmax_activity(np.zeros((3, 3)), np.full((3, 3), 1 / 3))
+
+
+@pytest.mark.parametrize("recipe,M,alpha,K,R", [("two_tier_10", 8, 0.1, 20, 8), ("four_group_12", 16, 0.05, 40, 6),
+                                                ("lognormal_1p5", 12, 0.1, 60, 8)])
+def test_generated_rows_satisfy_the_optimality_conditions_of_the_second_stage(recipe, M, alpha, K, R):
+    """Without enumerating supports (which both the library and the oracle do): on the returned policy every row's
+    surplus over the lower bounds of (o3), q_m = p_im - alpha rho (d_im + d_mi), is the least-squares point of the
+    optimal face, i.e. q_m = max(0, mu + nu t_im) for two multipliers.  The multipliers are fitted on the links
+    with a positive surplus and then have to explain the links without one (mu + nu t_im <= 0 there)."""
+    t = iteration_times(recipe, M)
+    got = nm.netmax_generate_policy(t, alpha, K, R)
+    P, rho = got["P"], got["rho"]
+    rows_with_choice = 0
+    for i in range(M):
+        nb = np.array([m for m in range(M) if m != i])
+        q = P[i, nb] - 2.0 * alpha * rho
+        assert q.min() > -1e-12
+        on = q > 1e-10
+        if on.sum() < 2:
+            continue
+        A = np.stack([np.ones(on.sum()), t[i, nb][on]], axis=1)
+        (mu, nu), *_ = np.linalg.lstsq(A, q[on], rcond=None)
+        np.testing.assert_allclose(A @ np.array([mu, nu]), q[on], atol=1e-9)
+        assert np.all(mu + nu * t[i, nb][~on] <= 1e-9)
+        rows_with_choice += 1
+    assert rows_with_choice > 0
