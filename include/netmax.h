@@ -169,7 +169,14 @@ int netmax_mix(netmax_ctx *ctx, uint64_t iter, const int32_t *peers_dev);
  * replayed (the iteration number then lives in a device cell that the graph advances), which removes the launch
  * overhead that dominates small models; this needs a context created on a non-default stream (the null stream
  * cannot be captured), else NETMAX_ESTATE.  The graphs are dropped when buffers, data or the learning rate change.
- * Results are identical to the individual calls. */
+ * Results are identical to the individual calls.
+ * Small softmax-regression models (one layer, float features, at most 32 classes, parameters and batch within a
+ * workgroup's LDS) run whole iterations inside ONE kernel, one workgroup per worker: without use_graph all n_iters
+ * iterations are one cooperative launch with a device-wide barrier after every iteration (when all M workgroups fit
+ * the device at once, else one launch per iteration); with use_graph the replayed graph holds that kernel.  Same
+ * results bit for bit: netmax_local_step runs the same gradient code for such models and every kernel applies the
+ * update with the same instructions.  Should a workgroup ever wait at the barrier in vain, the kernel still ends, the
+ * parameters are invalid and the next netmax_consensus_dist returns NETMAX_EDEVICE. */
 int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *peers_dev, int32_t use_graph);
 
 /* netmax_run with the second-step update (Eq. (c0)/(c1)) applied by the weight-gradient kernels themselves: for the

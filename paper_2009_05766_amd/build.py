@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libnetmax.so")
 
-SOURCES = ["netmax_api.hip", "k_sample.hip", "k_synth_grad.hip", "k_mix.hip", "k_consensus.hip", "k_grad_mlp.hip",
+SOURCES = ["netmax_api.hip", "k_small_iter.hip", "k_sample.hip", "k_synth_grad.hip", "k_mix.hip", "k_consensus.hip", "k_grad_mlp.hip",
            "k_layout.hip", "k_grad_mfma.hip", "policy.hip", "k_async.hip", "k_mix_subset.hip", "k_mix_synth.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

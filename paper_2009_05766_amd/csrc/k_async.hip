@@ -60,9 +60,9 @@ __global__ void __launch_bounds__(256) async_row_kernel(int M, int64_t D, float 
         } else {
             g = load4(G + own + q);
         }
-        const f32x4 vn = mu * v + g + wd * x;
-        const f32x4 h = x - alpha * vn;
-        store4(X + own + q, h - wi * (h - xp));
+        f32x4 xn, vn;
+        momentum_mix4(x, v, g, xp, wi, alpha, mu, wd, xn, vn);
+        store4(X + own + q, xn);
         store4(V + own + q, vn);
     }
 }

@@ -11,6 +11,7 @@
 #include "bf16.h"
 #include "kernels.h"
 #include "layout.h"
+#include "vec.h"
 
 namespace netmax {
 
@@ -640,9 +641,9 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
         const f32x4_t xp = *reinterpret_cast<const f32x4_t *>(mx.Xcur + other);
         const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(mx.V + own));
         const f32x4_t gr = *reinterpret_cast<const f32x4_t *>(&T[row][cq]);
-        const f32x4_t vn = mx.mu * v + gr + mx.wd * x;
-        const f32x4_t h = x - mx.alpha * vn;
-        __builtin_nontemporal_store(h - wi * (h - xp), reinterpret_cast<f32x4_t *>(mx.Xnext + own));
+        f32x4_t xn, vn;
+        momentum_mix4(x, v, gr, xp, wi, mx.alpha, mx.mu, mx.wd, xn, vn);
+        __builtin_nontemporal_store(xn, reinterpret_cast<f32x4_t *>(mx.Xnext + own));
         __builtin_nontemporal_store(vn, reinterpret_cast<f32x4_t *>(mx.V + own));
     }
 }

@@ -87,11 +87,8 @@ mix_kernel(int M, int64_t n_tiles, const float *__restrict__ Xcur, const float *
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
-        for (int u = 0; u < MIX_VECS; ++u) {
-            vo[s][u] = mu * rv[s][u] + rg[s][u] + wd * rx[s][u];             // v' = mu v + g + wd x
-            const f32x4 h = rx[s][u] - alpha * vo[s][u];                     // first-step update
-            xo[s][u] = h - wi[s] * (h - rp[s][u]);                           // second-step update towards the peer
-        }
+        for (int u = 0; u < MIX_VECS; ++u)
+            momentum_mix4(rx[s][u], rv[s][u], rg[s][u], rp[s][u], wi[s], alpha, mu, wd, xo[s][u], vo[s][u]);
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s)
         if (live[s])

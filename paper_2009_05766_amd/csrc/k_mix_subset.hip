@@ -27,9 +27,9 @@ mix_subset_kernel(int M, const int32_t *__restrict__ tiles, MixSkip skip, const 
         if (left_out) continue;
         const f32x4 x = load4(Xcur + own + q), xp = load4(Xcur + other + q);
         const f32x4 v = load4_stream(V + own + q), g = load4_stream(G + own + q);
-        const f32x4 vn = mu * v + g + wd * x;
-        const f32x4 h = x - alpha * vn;
-        store4_stream(Xnext + own + q, h - wi * (h - xp));
+        f32x4 xn, vn;
+        momentum_mix4(x, v, g, xp, wi, alpha, mu, wd, xn, vn);
+        store4_stream(Xnext + own + q, xn);
         store4_stream(V + own + q, vn);
     }
 }

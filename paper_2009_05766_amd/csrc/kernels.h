@@ -4,9 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "philox.h"   // IterRef: iteration number by value or from a device cell
+
 namespace netmax {
 
-struct IterRef;   // philox.h: iteration number by value or from a device cell
 
 // Peer selection of Algorithm 2: one Philox draw per worker against fixed-point cumulative thresholds.
 void launch_sample_peers(hipStream_t s, int M, const uint32_t *thr, const int32_t *last, uint64_t seed,
@@ -73,6 +74,24 @@ void launch_unpack(hipStream_t s, int M, int64_t cols, const float *tiled, float
 
 // out[k] = bfloat16 in[k] as float, k < n.
 void launch_widen_bf16(hipStream_t s, int64_t n, const uint16_t *in, float *out);
+
+// Whole iterations of a small softmax-regression model in one kernel, one workgroup per worker (k_small_iter.hip).
+// grad_only: batch draw, loss and gradient only (G, loss, idx); otherwise also the peer draw (peers) and the update
+// (x_second, V).  n_iters > 1 needs a cooperative launch: x_first / x_second swap roles after every iteration and
+// the workgroups meet at a barrier (counter `barrier`, which the launch advances by (n_iters - 1) * M from
+// barrier_base); *fault is raised if a workgroup waited in vain.
+struct SmallIterLaunch {
+    int M, B; int64_t din, dout, D, ld;
+    const float *feats; const int32_t *labels; const int64_t *row0; const int32_t *n_rows;
+    const uint32_t *thr; const int32_t *last; const float *w;
+    float *x_first, *x_second, *V, *G, *loss; int32_t *peers, *idx;
+    float alpha, mu, wd; uint64_t seed; IterRef iter; int n_iters, grad_only;
+    unsigned *barrier; unsigned barrier_base; int *fault;
+};
+bool small_iter_ok(int model_is_mlp, int n_layers, int bf16, int B, int64_t din, int64_t dout, int64_t ld);
+hipError_t prepare_small_iter();
+int small_iter_max_resident(int B, int64_t din, int64_t dout, int64_t ld);
+hipError_t launch_small_iter(hipStream_t s, const SmallIterLaunch &a, int cooperative);
 
 // Per-worker MLP / softmax-regression gradient (grouped GEMMs).
 struct MlpPlan {

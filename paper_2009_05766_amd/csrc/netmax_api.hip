@@ -5,6 +5,7 @@
 #include "layout.h"
 #include "philox.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -57,6 +58,12 @@ struct netmax_ctx {
     uint32_t *d_act_thr = nullptr;
     int act_last = -1;
     uint64_t iterations = 0;
+    // small softmax-regression models: whole iterations in one kernel (k_small_iter.hip)
+    bool small = false;                       // the model qualifies
+    int small_resident = 0;                   // workgroups of that kernel the device holds at once (cooperative runs)
+    unsigned *d_barrier = nullptr;            // grid-barrier counter, only ever advanced
+    unsigned barrier_count = 0;               // its value once everything enqueued so far has run
+    int *d_fault = nullptr;                   // raised by a workgroup that waited at the barrier in vain
     // graph replay (netmax_run): one captured iteration per direction of the parameter ping-pong
     float *x_first = nullptr;                 // the buffer bound as x_a: decides which graph an iteration uses
     uint64_t *d_iter = nullptr;               // device cell holding the iteration number of the next replay
@@ -206,6 +213,7 @@ static void release(netmax_ctx *ctx)
     for (auto *p : ctx->d_dzt) (void)hipFree(p);
     (void)hipFree(ctx->d_partial); (void)hipFree(ctx->d_cd);
     (void)hipFree(ctx->d_act_thr); (void)hipFree(ctx->d_fuse_tiles);
+    (void)hipFree(ctx->d_barrier); (void)hipFree(ctx->d_fault);
     delete ctx;
 }
 
@@ -331,6 +339,15 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
         INIT_TRY(hipMalloc(&ctx->d_nrows, M * sizeof(int32_t)));
         INIT_TRY(hipMalloc(&ctx->d_loss, M * sizeof(float)));
         INIT_TRY(hipMalloc(&ctx->d_flag, sizeof(int32_t)));
+        ctx->small = small_iter_ok(1, cfg->n_layers, cfg->gemm_in == NETMAX_BF16, cfg->batch, cfg->dims[0], cfg->dims[1], cfg->ld);
+        if (ctx->small) {
+            INIT_TRY(prepare_small_iter());
+            ctx->small_resident = small_iter_max_resident(cfg->batch, cfg->dims[0], cfg->dims[1], cfg->ld);
+            INIT_TRY(hipMalloc(&ctx->d_barrier, sizeof(unsigned)));
+            INIT_TRY(hipMalloc(&ctx->d_fault, sizeof(int)));
+            INIT_TRY(hipMemset(ctx->d_barrier, 0, sizeof(unsigned)));
+            INIT_TRY(hipMemset(ctx->d_fault, 0, sizeof(int)));
+        }
     }
 #undef INIT_TRY
     rc = upload_tables(ctx);
@@ -500,6 +517,26 @@ static MixArgs mix_args(const netmax_ctx *ctx, const int32_t *peers_dev)
     return MixArgs{ctx->x_cur, ctx->v, ctx->x_next, peers_dev, ctx->d_w, c.lr, c.momentum, c.weight_decay};
 }
 
+// Small softmax-regression models: n_iters whole iterations (or, grad_only, one batch draw + loss + gradient) in one
+// launch of the one-workgroup-per-worker kernel.  No pointer flip here.
+static int enqueue_small(netmax_ctx *ctx, const IterRef &iter, int n_iters, bool grad_only, int32_t *peers_dev, bool cooperative)
+{
+    const netmax_config &c = ctx->cfg;
+    SmallIterLaunch a{};
+    a.M = c.M; a.B = c.batch; a.din = c.dims[0]; a.dout = c.dims[1]; a.D = c.D; a.ld = c.ld;
+    a.feats = (const float *)ctx->feats; a.labels = ctx->labels; a.row0 = ctx->d_row0; a.n_rows = ctx->d_nrows;
+    a.thr = ctx->d_thr; a.last = ctx->d_last; a.w = ctx->d_w;
+    a.x_first = ctx->x_cur; a.x_second = ctx->x_next; a.V = ctx->v; a.G = ctx->g; a.loss = ctx->d_loss;
+    a.peers = peers_dev; a.idx = ctx->d_idx;
+    a.alpha = c.lr; a.mu = c.momentum; a.wd = c.weight_decay; a.seed = c.seed; a.iter = iter; a.n_iters = n_iters;
+    a.grad_only = grad_only ? 1 : 0;
+    a.barrier = ctx->d_barrier; a.barrier_base = ctx->barrier_count; a.fault = ctx->d_fault;
+    const hipError_t e = launch_small_iter(ctx->stream, a, cooperative ? 1 : 0);
+    if (e != hipSuccess) return fail(ctx, NETMAX_EDEVICE, std::string("small-model iteration kernel: ") + hipGetErrorString(e));
+    if (n_iters > 1) ctx->barrier_count += (unsigned)(n_iters - 1) * (unsigned)c.M;
+    return NETMAX_OK;
+}
+
 // fused_peers != nullptr: the matrix-core layers apply the update to their weight columns themselves (netmax_run
 // after netmax_set_fusion); enqueue_mix then covers the remaining columns only.
 static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_t *fused_peers = nullptr)
@@ -510,6 +547,7 @@ static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_
         launch_synth_grad(ctx->stream, c.M, c.D, c.ld, c.grad_sigma, c.seed, iter, ctx->g);
         return check_launch(ctx, "synth_grad");
     }
+    if (ctx->small) return enqueue_small(ctx, iter, 1, true, nullptr, false);
     launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
     const MlpPlan p = make_plan(ctx);
     if (fused_peers) {
@@ -588,9 +626,14 @@ static int capture_iteration(netmax_ctx *ctx, int dir, int32_t *peers_dev)
     hipGraph_t graph = nullptr;
     HIP_TRY(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal));
     const IterRef it{0, ctx->d_iter};
-    int rc = enqueue_sample_peers(ctx, it, peers_dev);
-    if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
-    if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse, it);
+    int rc;
+    if (ctx->small && !ctx->fuse) {
+        rc = enqueue_small(ctx, it, 1, false, peers_dev, false);
+    } else {
+        rc = enqueue_sample_peers(ctx, it, peers_dev);
+        if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
+        if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse, it);
+    }
     if (rc == NETMAX_OK) {
         launch_bump_iteration(ctx->stream, ctx->d_iter);
         rc = check_launch(ctx, "bump_iteration");
@@ -616,6 +659,20 @@ extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters,
     if (!ctx->x_cur) return fail(ctx, NETMAX_ESTATE, "no state bound");
     if (ctx->cfg.model == NETMAX_MLP && !ctx->data_bound) return fail(ctx, NETMAX_ESTATE, "no data bound");
     if (!peers_dev || n_iters < 0) return fail(ctx, NETMAX_EINVAL, "peers_dev is NULL or n_iters < 0");
+    if (!use_graph && ctx->small && !ctx->fuse) {
+        // whole iterations inside one kernel; as many per launch as a cooperative launch allows (all workgroups
+        // resident), else one launch per iteration
+        const bool coop = ctx->small_resident >= ctx->cfg.M;
+        int32_t k = 0;
+        while (k < n_iters) {
+            const int32_t n = coop ? std::min<int32_t>(n_iters - k, 1 << 20) : 1;
+            const int rc = enqueue_small(ctx, IterRef{first_iter + (uint64_t)k, nullptr}, n, false, peers_dev, coop && n > 1);
+            if (rc != NETMAX_OK) return rc;
+            for (int32_t q = 0; q < n; ++q) flip(ctx);
+            k += n;
+        }
+        return NETMAX_OK;
+    }
     if (!use_graph) {
         for (int32_t k = 0; k < n_iters; ++k) {
             const IterRef it{first_iter + (uint64_t)k, nullptr};
@@ -819,7 +876,10 @@ extern "C" int netmax_consensus_dist(netmax_ctx *ctx, double *out_host)
     const int rc = check_launch(ctx, "consensus");
     if (rc != NETMAX_OK) return rc;
     HIP_TRY(ctx, hipMemcpyAsync(out_host, ctx->d_cd, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    int fault = 0;
+    if (ctx->d_fault) HIP_TRY(ctx, hipMemcpyAsync(&fault, ctx->d_fault, sizeof fault, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (fault) return fail(ctx, NETMAX_EDEVICE, "a multi-iteration launch of netmax_run lost its grid barrier: the parameters are not valid");
     return NETMAX_OK;
 }
 

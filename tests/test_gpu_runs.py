@@ -726,3 +726,47 @@ def test_random_small_configurations_run_modes(seed):
         assert rel_err_rows(calls.get("x").cpu().numpy(), o.X) < tol
         for g in (calls, eager, graph):
             g.close()
+
+
+@pytest.mark.parametrize("over,T", [(dict(), 100),                                                  # cfg1 itself, its whole horizon
+                                    (dict(M=2, dims=(7, 3), batch=1, n_per_worker=5), 12),
+                                    (dict(M=5, dims=(33, 32), batch=37, n_per_worker=90), 12),    # 32 classes, odd widths
+                                    (dict(M=64, dims=(256, 10), batch=32, n_per_worker=64), 30),
+                                    (dict(M=200, dims=(100, 12), batch=20, n_per_worker=40), 9),
+                                    (dict(M=300, dims=(64, 5), batch=8, n_per_worker=16), 6)])    # more workers than compute units
+def test_small_model_iterations_in_one_kernel(over, T):
+    """Softmax-regression models small enough for a workgroup's LDS run whole iterations inside one kernel: netmax_run
+    launches it once for all T iterations (cooperatively, a grid barrier per iteration) where all workers' workgroups
+    fit the device, else once per iteration.  Against the individual entry points (peer draw, local step with the same
+    gradient code, the mix kernel with the same update function): bit-identical x, v, g, peers, losses; against
+    the oracle: bit-exact peers, parameters within the run tolerance."""
+    w = workload("cfg1", **over)
+    inp = inputs_of(w)
+    if over:
+        inp["labels"] = np.minimum(inp["labels"], w.dims[-1] - 1).astype(np.int32)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        calls, one, graph, o = make_gpu(w, inp), make_gpu(w, inp), make_gpu(w, inp), make_oracle(w, inp)
+        import oracle
+        oracle.set_threads(8)
+        for it in range(T):
+            calls.step(it)
+            assert np.array_equal(calls.peers.cpu().numpy(), o.step(it))
+        one.run(0, T - 3)                      # one launch
+        one.run(T - 3, 1)                      # a single iteration: the same kernel without a barrier
+        one.run(T - 2, 2)
+        graph.run(0, T, use_graph=True)        # replayed graph of the one-kernel iteration
+        side.synchronize()
+        for other in (one, graph):
+            for what in ("x", "v", "g"):
+                assert np.array_equal(calls.get(what).cpu().numpy(), other.get(what).cpu().numpy()), (over, what)
+            assert np.array_equal(calls.peers.cpu().numpy(), other.peers.cpu().numpy())
+            assert np.array_equal(calls.losses().cpu().numpy(), other.losses().cpu().numpy())
+        X = calls.get("x").cpu().numpy()
+        assert rel_err_rows(X, o.X) < TOL_RUN
+        assert max_abs_err(X, o.X) <= TOL_RUN * np.abs(o.X).max()
+        np.testing.assert_allclose(calls.losses().cpu().numpy(), o.loss, rtol=1e-4)
+        assert one.consensus_dist() == pytest.approx(o.consensus_dist(), rel=1e-4)   # also reads the barrier's fault flag
+        oracle.set_threads(1)
+        for g in (calls, one, graph):
+            g.close()
