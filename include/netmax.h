@@ -206,10 +206,13 @@ int netmax_set_fusion(netmax_ctx *ctx, int32_t on);
  * netmax_async_run: global steps first_step .. first_step + n_steps - 1 on the context's stream.  Step k draws i_k
  * from word 0 of Philox stream 3 at counter (0, 0, k) and m_k from stream 0 at counter (0, i_k, k); the gradient
  * of the active worker uses iteration number k in its counters.  active_dev / peers_dev: device int32 [n_steps],
- * caller-owned, receive i_k and m_k.  x (the current buffer) and v are updated in place, no buffer flip; g
- * receives the gradient (for perceptron models the gradient kernels compute all workers' rows and the active one is
- * used).  Needs netmax_bind_state, netmax_set_activity and, for perceptron models, netmax_bind_data
- * (else NETMAX_ESTATE).  Returns after enqueueing. */
+ * caller-owned, receive i_k and m_k.  x (the current buffer) and v are updated in place, no buffer flip; the active
+ * worker's row of g receives its gradient (only that worker's gradient is computed).  Consecutive steps that cannot
+ * see each other (no worker active twice, no pull from a row written earlier in the group, no write to a row pulled
+ * earlier) run as one batch of launches of up to 32 steps; the host finds these groups by repeating the draws, which
+ * are integer work on the same tables.  The result is that of the strictly sequential schedule.
+ * Needs netmax_bind_state, netmax_set_activity and, for perceptron models, netmax_bind_data (else NETMAX_ESTATE).
+ * Returns after enqueueing. */
 int netmax_activity(int32_t M, const double *t_host, const double *P_host, const uint8_t *adj, double *p_act_out);
 int netmax_mean_times(int32_t M, const double *t_host, const double *P_host, const uint8_t *adj, double *tbar_out,
                       double *rate_out);

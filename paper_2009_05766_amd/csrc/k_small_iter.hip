@@ -48,6 +48,7 @@ struct SmallIterArgs {
     IterRef iter;                           // number of the first iteration
     int n_iters, grad_only;
     unsigned *barrier; unsigned barrier_base; int *fault;
+    const int32_t *workers;                 // grad_only: workgroup s works for worker workers[s] at iteration iter + s (NULL: s, iter)
 };
 
 static int small_iter_cap(int64_t dout) { return dout <= 8 ? 8 : (dout <= 16 ? 16 : SI_MAX_OUT); }
@@ -117,7 +118,9 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
     constexpr int OWN = CAP / SI_SPLIT;                       // classes a lane owns after the reduction of a row
     constexpr int WP = CAP + 4;                               // floats per padded row of W: the eight rows a wave reads
                                                               // together then lie in different LDS banks
-    const int t0 = threadIdx.x, i = blockIdx.x;
+    const int t0 = threadIdx.x;
+    const int i = p.workers ? p.workers[blockIdx.x] : (int)blockIdx.x;
+    if ((unsigned)i >= (unsigned)p.M) return;
     const int pitch = p.din + SI_SPLIT;
     float *xl = reinterpret_cast<float *>(si_smem);           // [ld]  the worker's parameters (W row-major [din][dout], b)
     float *gl = xl + p.ld;                                    // [ld]  its gradient
@@ -129,7 +132,7 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
     int32_t *ib = reinterpret_cast<int32_t *>(lb + p.B);      // [2][B] batch rows (shard-local) of this and the next iteration
     int32_t *yl = ib + 2 * p.B;                               // [2][B] their labels
     int32_t *cnt = yl + 2 * p.B;                              // [2] thresholds of the peer draw that are <= u
-    const uint64_t iter0 = iteration_of(p.iter);
+    const uint64_t iter0 = iteration_of(p.iter) + (p.workers ? (uint64_t)blockIdx.x : 0ull);
     const int n_vec = (int)(p.ld >> 2);
     const float invB = 1.0f / (float)p.B;
     const uint32_t n_i = (uint32_t)p.n_rows[i];
@@ -483,11 +486,13 @@ hipError_t launch_small_iter(hipStream_t s, const SmallIterLaunch &a, int cooper
     p.x_first = a.x_first; p.x_second = a.x_second; p.V = a.V; p.G = a.G; p.loss = a.loss; p.peers = a.peers; p.idx = a.idx;
     p.alpha = a.alpha; p.mu = a.mu; p.wd = a.wd; p.seed = a.seed; p.iter = a.iter; p.n_iters = a.n_iters;
     p.grad_only = a.grad_only; p.barrier = a.barrier; p.barrier_base = a.barrier_base; p.fault = a.fault;
+    p.workers = a.grad_only ? a.workers : nullptr;
+    const unsigned groups = p.workers ? (unsigned)a.n_workers : (unsigned)a.M;
     const size_t lds = small_iter_lds(a.B, p.din, p.dout, a.ld);
     void *args[] = {&p};
     if (cooperative)
-        return hipLaunchCooperativeKernel(small_iter_kernel(a.dout), dim3((unsigned)a.M), dim3(SI_THREADS), args, (unsigned)lds, s);
-    return hipLaunchKernel(small_iter_kernel(a.dout), dim3((unsigned)a.M), dim3(SI_THREADS), args, lds, s);
+        return hipLaunchCooperativeKernel(small_iter_kernel(a.dout), dim3(groups), dim3(SI_THREADS), args, (unsigned)lds, s);
+    return hipLaunchKernel(small_iter_kernel(a.dout), dim3(groups), dim3(SI_THREADS), args, lds, s);
 }
 
 // How many workgroups of the kernel fit on the device at once with this much LDS each (0 if unknown).

@@ -24,9 +24,19 @@ void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma,
 // Asynchronous schedule: all (active worker, peer) draws of a run, and the in-place update of one worker's row.
 void launch_async_draw(hipStream_t s, int M, const uint32_t *act_thr, int act_last, const uint32_t *thr, const int32_t *last,
                        uint64_t seed, uint64_t first, uint64_t n_steps, int32_t *active, int32_t *peers);
-void launch_async_row(hipStream_t s, bool synth, int M, int64_t D, int64_t ld, float *X, float *V, float *G,
-                      const int32_t *active, const int32_t *peers, const float *w, float alpha, float mu, float wd,
-                      float sigma, uint64_t seed, uint64_t k);
+// A batch of n_steps consecutive global steps (numbers k0, k0 + 1, ...) whose rows do not overlap.  source 0: flat model,
+// gradient generated; 1: read from the active worker's row of G; 2: read from slot s of the compact matrix Gc.
+void launch_async_rows(hipStream_t s, int source, int M, int64_t D, int64_t ld, float *X, float *V, float *G, const float *Gc,
+                       int n_steps, const int32_t *active, const int32_t *peers, const float *w, float alpha, float mu, float wd,
+                       float sigma, uint64_t seed, uint64_t k0);
+// Subset runs of the perceptron gradient (asynchronous schedule): rows of listed workers into a compact matrix, their
+// shard descriptors, their batch draws (slot s at iteration first_iter + s), their losses back.
+void launch_gather_rows(hipStream_t s, int M, int n, int64_t ld, const int32_t *workers, const float *X, float *Xc);
+void launch_gather_shards(hipStream_t s, int M, int n, const int32_t *workers, const int64_t *row0, const int32_t *n_rows,
+                          int64_t *row0_c, int32_t *n_rows_c);
+void launch_scatter_loss(hipStream_t s, int M, int n, const int32_t *workers, const float *loss_c, float *loss);
+void launch_sample_batch_subset(hipStream_t s, int n, int B, const int32_t *workers, const int32_t *n_rows_c, uint64_t seed,
+                                uint64_t first_iter, int32_t *idx);
 
 void launch_async_times(hipStream_t s, int M, int64_t n_steps, const int32_t *active, const int32_t *peers, const float *t,
                         float beta, float *ema, float *clock);
@@ -87,6 +97,7 @@ struct SmallIterLaunch {
     float *x_first, *x_second, *V, *G, *loss; int32_t *peers, *idx;
     float alpha, mu, wd; uint64_t seed; IterRef iter; int n_iters, grad_only;
     unsigned *barrier; unsigned barrier_base; int *fault;
+    const int32_t *workers; int n_workers;   // grad_only: one workgroup per listed worker (device list), slot s at iteration iter + s
 };
 bool small_iter_ok(int model_is_mlp, int n_layers, int bf16, int B, int64_t din, int64_t dout, int64_t ld);
 hipError_t prepare_small_iter();

@@ -56,7 +56,13 @@ struct netmax_ctx {
     MixSkip fuse_skip{};
     // asynchronous schedule: thresholds of the activity probabilities p_i
     uint32_t *d_act_thr = nullptr;
+    std::vector<uint32_t> h_act_thr;          // host image: the host plans the batches of independent steps from the same draws
     int act_last = -1;
+    // perceptron gradients of a few listed workers (batches of the asynchronous schedule): compact copies
+    int sub_cap = 0;                          // slots allocated
+    float *d_xc = nullptr, *d_gc = nullptr, *d_lossc = nullptr;
+    int64_t *d_row0c = nullptr;
+    int32_t *d_nrowsc = nullptr;
     uint64_t iterations = 0;
     // small softmax-regression models: whole iterations in one kernel (k_small_iter.hip)
     bool small = false;                       // the model qualifies
@@ -214,6 +220,7 @@ static void release(netmax_ctx *ctx)
     (void)hipFree(ctx->d_partial); (void)hipFree(ctx->d_cd);
     (void)hipFree(ctx->d_act_thr); (void)hipFree(ctx->d_fuse_tiles);
     (void)hipFree(ctx->d_barrier); (void)hipFree(ctx->d_fault);
+    (void)hipFree(ctx->d_xc); (void)hipFree(ctx->d_gc); (void)hipFree(ctx->d_lossc); (void)hipFree(ctx->d_row0c); (void)hipFree(ctx->d_nrowsc);
     delete ctx;
 }
 
@@ -519,7 +526,7 @@ static MixArgs mix_args(const netmax_ctx *ctx, const int32_t *peers_dev)
 
 // Small softmax-regression models: n_iters whole iterations (or, grad_only, one batch draw + loss + gradient) in one
 // launch of the one-workgroup-per-worker kernel.  No pointer flip here.
-static int enqueue_small(netmax_ctx *ctx, const IterRef &iter, int n_iters, bool grad_only, int32_t *peers_dev, bool cooperative)
+static SmallIterLaunch small_launch(netmax_ctx *ctx, const IterRef &iter, int n_iters, bool grad_only, int32_t *peers_dev)
 {
     const netmax_config &c = ctx->cfg;
     SmallIterLaunch a{};
@@ -531,9 +538,16 @@ static int enqueue_small(netmax_ctx *ctx, const IterRef &iter, int n_iters, bool
     a.alpha = c.lr; a.mu = c.momentum; a.wd = c.weight_decay; a.seed = c.seed; a.iter = iter; a.n_iters = n_iters;
     a.grad_only = grad_only ? 1 : 0;
     a.barrier = ctx->d_barrier; a.barrier_base = ctx->barrier_count; a.fault = ctx->d_fault;
+    a.workers = nullptr; a.n_workers = 0;
+    return a;
+}
+
+static int enqueue_small(netmax_ctx *ctx, const IterRef &iter, int n_iters, bool grad_only, int32_t *peers_dev, bool cooperative)
+{
+    const SmallIterLaunch a = small_launch(ctx, iter, n_iters, grad_only, peers_dev);
     const hipError_t e = launch_small_iter(ctx->stream, a, cooperative ? 1 : 0);
     if (e != hipSuccess) return fail(ctx, NETMAX_EDEVICE, std::string("small-model iteration kernel: ") + hipGetErrorString(e));
-    if (n_iters > 1) ctx->barrier_count += (unsigned)(n_iters - 1) * (unsigned)c.M;
+    if (n_iters > 1) ctx->barrier_count += (unsigned)(n_iters - 1) * (unsigned)ctx->cfg.M;
     return NETMAX_OK;
 }
 
@@ -812,8 +826,44 @@ extern "C" int netmax_set_activity(netmax_ctx *ctx, const double *p_act)
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));         // a running step may still read the old thresholds
     if (!ctx->d_act_thr) HIP_TRY(ctx, hipMalloc(&ctx->d_act_thr, (size_t)M * sizeof(uint32_t)));
     HIP_TRY(ctx, hipMemcpy(ctx->d_act_thr, thr.data(), (size_t)M * sizeof(uint32_t), hipMemcpyHostToDevice));
+    ctx->h_act_thr = thr;
     ctx->act_last = tail;
     return NETMAX_OK;
+}
+
+// Number of thresholds <= u, clamped to the last positive entry: the draw of the kernels, on the host.
+static int host_draw(const uint32_t *row, int n, int last, uint32_t u)
+{
+    const int pos = (int)(std::upper_bound(row, row + n, u) - row);
+    return pos < last ? pos : last;
+}
+
+constexpr int ASYNC_MAX_BATCH = 32;
+
+// The gradients of the n listed workers (device list `workers`, consecutive global steps from k0) into the compact
+// matrix d_gc: their rows and shard descriptors are gathered, the grouped kernels run on n groups.
+static int enqueue_subset_gradient(netmax_ctx *ctx, const int32_t *workers, int n, uint64_t k0)
+{
+    const netmax_config &c = ctx->cfg;
+    if (!ctx->sub_cap) {
+        const int cap = std::min<int>(c.M, ASYNC_MAX_BATCH);
+        HIP_TRY(ctx, hipMalloc(&ctx->d_xc, (size_t)cap * c.ld * sizeof(float)));
+        HIP_TRY(ctx, hipMalloc(&ctx->d_gc, (size_t)cap * c.ld * sizeof(float)));
+        HIP_TRY(ctx, hipMalloc(&ctx->d_lossc, (size_t)cap * sizeof(float)));
+        HIP_TRY(ctx, hipMalloc(&ctx->d_row0c, (size_t)cap * sizeof(int64_t)));
+        HIP_TRY(ctx, hipMalloc(&ctx->d_nrowsc, (size_t)cap * sizeof(int32_t)));
+        ctx->sub_cap = cap;
+    }
+    launch_gather_shards(ctx->stream, c.M, n, workers, ctx->d_row0, ctx->d_nrows, ctx->d_row0c, ctx->d_nrowsc);
+    launch_sample_batch_subset(ctx->stream, n, c.batch, workers, ctx->d_nrowsc, c.seed, k0, ctx->d_idx);
+    launch_gather_rows(ctx->stream, c.M, n, c.ld, workers, ctx->x_cur, ctx->d_xc);
+    MlpPlan p = make_plan(ctx);
+    p.M = n;
+    p.row0 = ctx->d_row0c;
+    p.loss = ctx->d_lossc;
+    launch_mlp_grad(ctx->stream, p, ctx->d_xc, ctx->d_gc);
+    launch_scatter_loss(ctx->stream, c.M, n, workers, ctx->d_lossc, ctx->d_loss);
+    return check_launch(ctx, "subset gradient");
 }
 
 extern "C" int netmax_async_run(netmax_ctx *ctx, uint64_t first_step, uint64_t n_steps, int32_t *active_dev, int32_t *peers_dev)
@@ -830,16 +880,49 @@ extern "C" int netmax_async_run(netmax_ctx *ctx, uint64_t first_step, uint64_t n
     launch_async_draw(ctx->stream, c.M, ctx->d_act_thr, ctx->act_last, ctx->d_thr, ctx->d_last, c.seed, first_step, n_steps,
                       active_dev, peers_dev);
     int rc = check_launch(ctx, "async_draw");
-    for (uint64_t s = 0; s < n_steps && rc == NETMAX_OK; ++s) {
-        const uint64_t k = first_step + s;
-        if (c.model == NETMAX_MLP) {
-            // the gradient kernels work on all workers at once; the active worker's row is the one that is used
-            rc = enqueue_local_step(ctx, IterRef{k, nullptr});
-            if (rc != NETMAX_OK) break;
+    // The host repeats the draws (integer work on the same tables) and cuts the run into batches of consecutive
+    // steps that cannot see each other: a step joins the batch unless its active worker was active or pulled
+    // from earlier in the batch, or it pulls from a worker that was active.  A batch is one set of launches.
+    const int cap = std::min<int>(c.M, ASYNC_MAX_BATCH);
+    std::vector<uint8_t> wrote(c.M, 0), read(c.M, 0);
+    std::vector<int> touched;
+    uint64_t s0 = 0;
+    while (s0 < n_steps && rc == NETMAX_OK) {
+        int n = 0;
+        touched.clear();
+        while (s0 + n < n_steps && n < cap) {
+            const uint64_t k = first_step + s0 + n;
+            const int i = host_draw(ctx->h_act_thr.data(), c.M, ctx->act_last, draw_block(c.seed, STREAM_ACTIVE, 0u, 0u, k).a);
+            const int m = host_draw(ctx->h_thr.data() + (size_t)i * c.M, c.M, ctx->h_last[i],
+                                    draw_block(c.seed, STREAM_PEER, 0u, (uint32_t)i, k).a);
+            if (n > 0 && (wrote[i] || read[i] || wrote[m])) break;
+            wrote[i] = 1;
+            read[m] = 1;
+            touched.push_back(i);
+            touched.push_back(m);
+            ++n;
         }
-        launch_async_row(ctx->stream, c.model == NETMAX_FLAT, c.M, c.D, c.ld, ctx->x_cur, ctx->v, ctx->g, active_dev + s,
-                         peers_dev + s, ctx->d_w, c.lr, c.momentum, c.weight_decay, c.grad_sigma, c.seed, k);
-        rc = check_launch(ctx, "async_row");
+        for (int q : touched) wrote[q] = read[q] = 0;
+        const uint64_t k0 = first_step + s0;
+        int source = 0;
+        if (c.model == NETMAX_MLP) {
+            if (ctx->small) {
+                SmallIterLaunch a = small_launch(ctx, IterRef{k0, nullptr}, 1, true, nullptr);
+                a.workers = active_dev + s0;
+                a.n_workers = n;
+                const hipError_t e = launch_small_iter(ctx->stream, a, 0);
+                if (e != hipSuccess) return fail(ctx, NETMAX_EDEVICE, std::string("small-model gradient kernel: ") + hipGetErrorString(e));
+                source = 1;
+            } else {
+                rc = enqueue_subset_gradient(ctx, active_dev + s0, n, k0);
+                if (rc != NETMAX_OK) break;
+                source = 2;
+            }
+        }
+        launch_async_rows(ctx->stream, source, c.M, c.D, c.ld, ctx->x_cur, ctx->v, ctx->g, ctx->d_gc, n, active_dev + s0,
+                          peers_dev + s0, ctx->d_w, c.lr, c.momentum, c.weight_decay, c.grad_sigma, c.seed, k0);
+        rc = check_launch(ctx, "async_rows");
+        s0 += (uint64_t)n;
     }
     if (rc == NETMAX_OK) ctx->iterations = first_step + n_steps;
     return rc;

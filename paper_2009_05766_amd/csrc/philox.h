@@ -1,4 +1,5 @@
-// Philox4x32-10 (Salmon et al., SC'11) for device code: 4 x u32 counter, 2 x u32 key, ten rounds,
+// Philox4x32-10 (Salmon et al., SC'11), device code (and the host, which plans the asynchronous schedule's
+// batches from the same draws): 4 x u32 counter, 2 x u32 key, ten rounds,
 // key bumped by the Weyl constants between rounds.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -8,7 +9,7 @@ namespace netmax {
 
 struct Words4 { uint32_t a, b, c, d; };
 
-__device__ __forceinline__ Words4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+__host__ __device__ __forceinline__ Words4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                 uint32_t k0, uint32_t k1)
 {
     constexpr uint32_t MUL_A = 0xD2511F53u, MUL_B = 0xCD9E8D57u;
@@ -36,7 +37,7 @@ __device__ __forceinline__ uint64_t iteration_of(IterRef r) { return r.cell ? *r
 // The library's draws: key = (seed_lo, seed_hi ^ stream), counter = (block, worker, iter_lo, iter_hi).
 enum : uint32_t { STREAM_PEER = 0u, STREAM_BATCH = 1u, STREAM_GRAD = 2u, STREAM_ACTIVE = 3u };
 
-__device__ __forceinline__ Words4 draw_block(uint64_t seed, uint32_t stream, uint32_t block, uint32_t worker,
+__host__ __device__ __forceinline__ Words4 draw_block(uint64_t seed, uint32_t stream, uint32_t block, uint32_t worker,
                                              uint64_t iter)
 {
     return philox4x32_10(block, worker, (uint32_t)iter, (uint32_t)(iter >> 32), (uint32_t)seed,

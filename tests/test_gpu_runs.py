@@ -478,7 +478,11 @@ def test_async_schedule_flat():
     gpu.close()
 
 
-@pytest.mark.parametrize("name,over", [("cfg1", dict()), ("cfg5", dict(M=4, n_per_worker=128, dims=(256, 128, 128, 10), batch=64))])
+@pytest.mark.parametrize("name,over", [("cfg1", dict()), ("cfg5", dict(M=4, n_per_worker=128, dims=(256, 128, 128, 10), batch=64)),
+                                       # more workers: several independent global steps per batch of launches
+                                       ("cfg1", dict(M=40, n_per_worker=64, dims=(24, 10), batch=8)),
+                                       ("cfg2", dict(M=16, n_per_worker=64, dims=(40, 24, 10), batch=16)),
+                                       ("cfg5", dict(M=12, n_per_worker=128, dims=(256, 128, 128, 10), batch=64))])
 def test_async_schedule_perceptron(name, over):
     import paper_2009_05766_amd as nm
     w = workload(name, **over)
@@ -499,6 +503,29 @@ def test_async_schedule_perceptron(name, over):
         assert np.array_equal(peers[k0:k0 + 6].cpu().numpy(), want[:, 1])
         worst = max(worst, rel_err_rows(gpu.get("x").cpu().numpy(), o.X))
     assert worst < (1e-3 if bf else TOL_RUN), worst
+    gpu.close()
+
+
+def test_async_schedule_flat_many_workers_in_batches():
+    """With many workers most consecutive global steps touch different rows; the library runs such steps as one
+    batch of launches.  Same draws, same rows as the oracle's strictly sequential steps, including the steps at which
+    a batch has to end (a worker active twice, a pull from a row just written, a write to a row just pulled)."""
+    import paper_2009_05766_amd as nm
+    w = workload("cfg3", M=64, D=3000, T=10)
+    inp = inputs_of(w)
+    gpu, o = _async_pair(w, inp)
+    n = 700
+    active = torch.zeros(n, dtype=torch.int32, device="cuda")
+    peers = torch.zeros(n, dtype=torch.int32, device="cuda")
+    nm.netmax_async_run(gpu.ctx, 0, n, active, peers)
+    want = np.array([o.async_step(k) for k in range(n)], dtype=np.int32)
+    assert np.array_equal(active.cpu().numpy(), want[:, 0]) and np.array_equal(peers.cpu().numpy(), want[:, 1])
+    # the run contains the conflicts that end a batch
+    a, m = want[:, 0], want[:, 1]
+    assert (a[1:] == a[:-1]).any() or (m[1:] == a[:-1]).any() or (a[1:] == m[:-1]).any()
+    assert rel_err_rows(gpu.get("x").cpu().numpy(), o.X) < TOL_RUN
+    assert rel_err_rows(gpu.get("v").cpu().numpy(), o.V) < TOL_RUN
+    assert max_abs_err(gpu.get("x").cpu().numpy(), o.X) <= TOL_RUN * np.abs(o.X).max()
     gpu.close()
 
 
