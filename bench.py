@@ -28,10 +28,10 @@ MIX_BYTES_MIN, MIX_BYTES_NAIVE = 20, 24
 # iteration_cfg5.md), each
 # counter scaled by what it reads for a plain device copy of known size.  Valid only for the kernel sources they
 # were taken with: keyed by the sha256 prefix of k_mix.hip + layout.h + vec.h, reported as null otherwise.
-_MIX_SOURCES = "39afcb9d2ad0854c.3f97687d5424e9a2.f872db49a5d92e6f"
-MEASURED_TRAFFIC = {"cfg3": {"sources": _MIX_SOURCES, "bytes": 14339318768},
-                    "cfg4": {"sources": _MIX_SOURCES, "bytes": 12802460032},
-                    "cfg5": {"sources": _MIX_SOURCES, "bytes": 10777684079}}
+_MIX_SOURCES = "c8b2061f1db7daaa.3f97687d5424e9a2.e54cf75f51c45279"
+MEASURED_TRAFFIC = {"cfg3": {"sources": _MIX_SOURCES, "bytes": 14338993040},
+                    "cfg4": {"sources": _MIX_SOURCES, "bytes": 12802386208},
+                    "cfg5": {"sources": _MIX_SOURCES, "bytes": 10778493919}}
 
 
 def mix_sources_digest() -> str:
