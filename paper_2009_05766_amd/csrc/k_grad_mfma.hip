@@ -442,9 +442,52 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
 // straight from the accumulators as 128-byte row pieces (non-temporal) into the gradient row.
 struct WgradMfmaArgs {
     const uint16_t *a_t, *dz_t; int M, B; int64_t din, dout, woff; float *G;
+    const uint16_t *feats; const int64_t *row0; const int32_t *idx;      // first layer: A^T is gathered from the data rows
 };
 
 constexpr int WG_PITCH = 128 + 8;            // bf16 elements per operand row in LDS (272 B)
+
+// The strip's A^T block [ROWS][B] into LDS.  Layers above the first read it from the transposed bf16 activations
+// (batch-contiguous rows, whole 16-byte chunks).  The first layer (feats != nullptr) takes it from the data rows of
+// the worker's batch themselves: every batch row holds the strip's ROWS features as ROWS * 2 contiguous bytes; a
+// thread loads eight of them and scatters them into eight rows of the block.  Neighbouring lanes take neighbouring
+// batch rows (the same feature chunk): their 2-byte LDS writes fall into one row of the block, and the eight chunks
+// of a data row's line are fetched from memory once and hit in the cache afterwards.
+template <int ROWS>
+__device__ __forceinline__ void load_at_block(uint16_t (*At)[WG_PITCH], int t, int g, int B, int64_t din, int64_t r0,
+                                              const uint16_t *a_t, const uint16_t *feats, const int64_t *row0,
+                                              const int32_t *idx)
+{
+    if (feats) {
+        constexpr int KC = ROWS / 8;                             // 16-byte chunks of a batch row inside the strip
+        constexpr int N = KC * 128 / MF_THREADS;                 // chunks per thread at the largest batch, all requested first
+        u32x4 v[N];
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            const int c = t + q * MF_THREADS, kc = c / B, b = c - kc * B;
+            if (c < KC * B)
+                v[q] = *reinterpret_cast<const u32x4 *>(feats + (size_t)(row0[g] + idx[(size_t)g * B + b]) * din + r0 + 8 * kc);
+        }
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            const int c = t + q * MF_THREADS, kc = c / B, b = c - kc * B;
+            if (c < KC * B) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    At[8 * kc + 2 * e][b] = (uint16_t)(v[q][e] & 0xFFFFu);
+                    At[8 * kc + 2 * e + 1][b] = (uint16_t)(v[q][e] >> 16);
+                }
+            }
+        }
+        return;
+    }
+    const int chunks_per_row = B >> 3;
+    const uint16_t *a_src = a_t + ((size_t)g * din + r0) * B;
+    for (int c = t; c < ROWS * chunks_per_row; c += MF_THREADS) {
+        const int row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
+        *reinterpret_cast<u32x4 *>(&At[row][col]) = *reinterpret_cast<const u32x4 *>(a_src + (size_t)row * B + col);
+    }
+}
 
 // STRIP: rows of W per workgroup (128 or 64), BN: columns per block step (128 or 64); waves 2 x 2, each
 // STRIP / 2 rows x BN / 2 columns.
@@ -453,7 +496,6 @@ template <int STRIP, int BN>
 __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
 {
     constexpr int RI = STRIP / 64;                               // 32-row tiles per wave
-    constexpr int A_CHUNKS = STRIP * 128 / 8 / MF_THREADS;       // 16-byte chunks per thread at B = 128
     constexpr int CJ = BN / 64;                                  // 32-column tiles per wave
     constexpr int Z_CHUNKS = BN * 128 / 8 / MF_THREADS;
     __shared__ __attribute__((aligned(16))) uint16_t At[STRIP][WG_PITCH];
@@ -465,15 +507,8 @@ __device__ __forceinline__ void wgrad_mfma_body(const WgradMfmaArgs &p)
     if (!decode_group(blockIdx.x, ny, p.M, g, strip)) return;
     const int64_t r0 = (int64_t)strip * STRIP;
     const int chunks_per_row = p.B >> 3;                        // 16-byte chunks; at most 16
-    const uint16_t *a_src = p.a_t + ((size_t)g * p.din + r0) * p.B;
     const uint16_t *z_src = p.dz_t + (size_t)g * p.dout * p.B;
-
-#pragma unroll
-    for (int q = 0; q < A_CHUNKS; ++q) {
-        const int c = t + q * MF_THREADS, row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
-        if (c < STRIP * chunks_per_row)
-            *reinterpret_cast<u32x4 *>(&At[row][col]) = *reinterpret_cast<const u32x4 *>(a_src + (size_t)row * p.B + col);
-    }
+    load_at_block<STRIP>(At, t, g, p.B, p.din, r0, p.a_t, p.feats, p.row0, p.idx);
     int c_row[Z_CHUNKS], c_col[Z_CHUNKS];
 #pragma unroll
     for (int q = 0; q < Z_CHUNKS; ++q) {
@@ -573,6 +608,7 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
 struct WgradMixArgs {
     const uint16_t *a_t, *dz_t; int M, B; int64_t din, dout, woff;
     MixArgs mix;
+    const uint16_t *feats; const int64_t *row0; const int32_t *idx;      // first layer: A^T is gathered from the data rows
 };
 constexpr int WM_ROWS = 64, WM_COLS = 128;
 constexpr int WM_TILE_PITCH = WM_COLS + 4;           // floats per staged row
@@ -593,14 +629,8 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
     if (blk >= blocks) return;
     const int64_t r0 = (int64_t)(blk / nbx) * WM_ROWS, n0 = (int64_t)(blk % nbx) * WM_COLS;
     const int chunks_per_row = p.B >> 3;
-    const uint16_t *a_src = p.a_t + ((size_t)g * p.din + r0) * p.B;
     const uint16_t *z_src = p.dz_t + ((size_t)g * p.dout + n0) * p.B;
-#pragma unroll
-    for (int q = 0; q < WM_ROWS * 16 / MF_THREADS; ++q) {
-        const int c = t + q * MF_THREADS, row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
-        if (c < WM_ROWS * chunks_per_row)
-            *reinterpret_cast<u32x4 *>(&At[row][col]) = *reinterpret_cast<const u32x4 *>(a_src + (size_t)row * p.B + col);
-    }
+    load_at_block<WM_ROWS>(At, t, g, p.B, p.din, r0, p.a_t, p.feats, p.row0, p.idx);
 #pragma unroll
     for (int q = 0; q < WM_COLS * 16 / MF_THREADS; ++q) {
         const int c = t + q * MF_THREADS, row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
@@ -645,47 +675,6 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
         momentum_mix4(x, v, gr, xp, wi, mx.alpha, mx.mu, mx.wd, xn, vn);
         __builtin_nontemporal_store(xn, reinterpret_cast<f32x4_t *>(mx.Xnext + own));
         __builtin_nontemporal_store(vn, reinterpret_cast<f32x4_t *>(mx.V + own));
-    }
-}
-
-// ---------------------------------------------------------------------------------------------------
-// Transposed bf16 copy of each worker's gathered batch: out[g][k][b] = feats[row0[g] + idx[g][b]][k].
-// One workgroup = one worker x 64 features; the tile is turned in LDS.
-__global__ void __launch_bounds__(256)
-gather_transpose_kernel(const uint16_t *__restrict__ feats, const int64_t *__restrict__ row0,
-                        const int32_t *__restrict__ idx, int B, int64_t din, uint16_t *__restrict__ out)
-{
-    __shared__ uint16_t tile[128][66];      // [b][k], pitch 33 words: conflict-free column reads
-    const int g = blockIdx.y, t = threadIdx.x;
-    const int64_t k0 = (int64_t)blockIdx.x * 64;
-    {
-        const int b = t >> 1, half = t & 1;
-        if (b < B) {
-            const uint16_t *src = feats + (row0[g] + idx[(size_t)g * B + b]) * din + k0 + 32 * half;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(src + 8 * c);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) *reinterpret_cast<uint32_t *>(&tile[b][32 * half + 8 * c + 2 * e]) = v[e];
-            }
-        }
-    }
-    __syncthreads();
-    {
-        const int k = t >> 2, bq = t & 3;       // 32 batch entries per thread
-        if (32 * bq < B) {
-            uint16_t *dst = out + ((size_t)g * din + k0 + k) * B + 32 * bq;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                u32x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int b = 32 * bq + 8 * c + 2 * e;
-                    v[e] = (uint32_t)tile[b][k] | ((uint32_t)tile[b + 1][k] << 16);
-                }
-                *reinterpret_cast<u32x4 *>(dst + 8 * c) = v;
-            }
-        }
     }
 }
 
@@ -891,12 +880,6 @@ void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, float *
     hipLaunchKernelGGL(dgrad_small_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / 128))), dim3(MF_THREADS), 0, s, a);
 }
 
-void launch_gather_transpose(hipStream_t s, const MlpPlan &p)
-{
-    hipLaunchKernelGGL(gather_transpose_kernel, dim3((unsigned)(p.dims[0] / 64), p.M), dim3(256), 0, s,
-                       (const uint16_t *)p.feats, p.row0, p.idx, p.B, p.dims[0], p.ht[0]);
-}
-
 void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X)
 {
     FwdMfmaArgs a;
@@ -921,6 +904,7 @@ void launch_wgrad_mix_mfma(hipStream_t s, const MlpPlan &p, int l, int cur, cons
     WgradMixArgs a;
     a.a_t = p.ht[l]; a.dz_t = p.dzt[cur]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.woff = p.woff[l]; a.mix = mix;
+    a.feats = l == 0 ? (const uint16_t *)p.feats : nullptr; a.row0 = p.row0; a.idx = p.idx;
     const unsigned blocks = (unsigned)((a.din / WM_ROWS) * (a.dout / WM_COLS));
     const unsigned grid = (blocks + MF_XCD - 1) / MF_XCD * MF_XCD * (unsigned)p.M;
     hipLaunchKernelGGL(wgrad_mix_mfma_kernel, dim3(grid), dim3(MF_THREADS), 0, s, a);
@@ -931,6 +915,7 @@ void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur
     WgradMfmaArgs a;
     a.a_t = p.ht[l]; a.dz_t = p.dzt[cur]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.woff = p.woff[l]; a.G = G;
+    a.feats = l == 0 ? (const uint16_t *)p.feats : nullptr; a.row0 = p.row0; a.idx = p.idx;
     hipLaunchKernelGGL(wgrad_mfma_kernel, dim3(grouped_grid(p.M, (unsigned)(a.din / WG_STRIP))), dim3(MF_THREADS), 0, s, a);
 }
 

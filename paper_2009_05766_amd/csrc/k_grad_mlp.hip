@@ -546,7 +546,6 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
         in.kind = l == 0 ? (bf ? IN_GATHER_BF16 : IN_GATHER_F32) : (bf ? IN_ACT_BF16 : IN_ACT_F32);
         return in;
     };
-    if (fast[0]) launch_gather_transpose(s, p);
     // forward.  With bf16 operands the hidden activations are kept as bfloat16 only (both orientations).
     for (int l = 0; l < L; ++l) {
         const bool last = (l + 1 == L);

@@ -120,7 +120,7 @@ struct MlpPlan {
     float *loss;            // [M]
     // bf16 operands only: bfloat16 copies of activations and back-propagated errors, in both orientations
     uint16_t *hb[8];        // hb[l], l = 1..n_layers-1: [M][B][dims[l]]
-    uint16_t *ht[8];        // ht[l], l = 0..n_layers-1: [M][dims[l]][B] (ht[0] = the gathered batch, transposed)
+    uint16_t *ht[8];        // ht[l], l = 1..n_layers-1: [M][dims[l]][B] (the first layer's weight gradient gathers its A^T from the data rows)
     uint16_t *dzb[2];       // [M][B][max width]
     uint16_t *dzt[2];       // [M][max width][B]
 };
@@ -135,7 +135,6 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
 
 // Matrix-core kernels (k_grad_mfma.hip) for layers that mfma_layer_ok() accepts.
 bool mfma_layer_ok(const MlpPlan &p, int l);
-void launch_gather_transpose(hipStream_t s, const MlpPlan &p);
 void launch_fwd_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X);
 // also writes the bias gradient of layer l - 1 into G; want_f32: keep the fp32 copy of the error as well
 void launch_dgrad_mfma(hipStream_t s, const MlpPlan &p, int l, const float *X, float *G, int cur, bool want_f32);

@@ -334,7 +334,7 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
         if (cfg->gemm_in == NETMAX_BF16) {
             for (int l = 0; l < cfg->n_layers; ++l) {
                 if (l > 0) INIT_TRY(hipMalloc(&ctx->d_hb[l], MB * cfg->dims[l] * sizeof(uint16_t)));
-                INIT_TRY(hipMalloc(&ctx->d_ht[l], MB * cfg->dims[l] * sizeof(uint16_t)));
+                if (l > 0) INIT_TRY(hipMalloc(&ctx->d_ht[l], MB * cfg->dims[l] * sizeof(uint16_t)));
             }
             for (int q = 0; q < 2; ++q) {
                 INIT_TRY(hipMalloc(&ctx->d_dzb[q], MB * widest * sizeof(uint16_t)));
