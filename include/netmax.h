@@ -190,6 +190,14 @@ int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters, int32_t *p
  * models without such a layer.  Waits for the stream and drops captured graphs. */
 int netmax_set_fusion(netmax_ctx *ctx, int32_t on);
 
+/* The device-wide barrier of the multi-iteration launches of netmax_run (small models, above) polls a counter; a
+ * workgroup that has polled `polls` times without seeing all others arrive raises the context's fault flag and goes
+ * on, so that the kernel always ends (default 2^24 polls, seconds; the barrier itself takes microseconds).  This call
+ * sets that number and clears the fault flag; it waits for the stream.  polls = 0 makes every workgroup that is not the
+ * last to arrive give up at once: the way to exercise the failure path (netmax_consensus_dist then returns
+ * NETMAX_EDEVICE and the parameters are not valid) without making anything wait. */
+int netmax_set_barrier_patience(netmax_ctx *ctx, int64_t polls);
+
 /* ---- Asynchronous schedule (Section II-B, Eq. (c2)-(c4)) ----------------------------------------------------
  * The workers do not step together: in global step k one worker i_k is active, pulls from m_k ~ P[i_k, :], takes
  * its local step and mixes; every other copy stays as it is, x^{k+1} = D^k (x^k - alpha g^k).  A worker whose

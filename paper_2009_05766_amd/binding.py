@@ -24,7 +24,7 @@ NETMAX_MIX_POLICY, NETMAX_MIX_FIXED = 0, 1
 
 EXPORTS = (
     "netmax_init", "netmax_build_tables", "netmax_generate_policy", "netmax_set_policy", "netmax_set_lr", "netmax_bind_state",
-    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_update_times_async", "netmax_activity", "netmax_mean_times", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion",
+    "netmax_bind_data", "netmax_pack", "netmax_unpack", "netmax_sample_peers", "netmax_sample_batch", "netmax_local_step", "netmax_mix", "netmax_run", "netmax_update_times", "netmax_update_times_async", "netmax_activity", "netmax_mean_times", "netmax_set_activity", "netmax_async_run", "netmax_set_fusion", "netmax_set_barrier_patience",
     "netmax_consensus_dist", "netmax_consensus_dist_static", "netmax_params", "netmax_losses", "netmax_read_losses", "netmax_read_hidden", "netmax_iteration", "netmax_get_tables",
     "netmax_last_error", "netmax_destroy",
 )
@@ -83,6 +83,7 @@ def load():
         "netmax_update_times": (C.c_int, [vp, vp, vp, f32, vp, vp]),
         "netmax_update_times_async": (C.c_int, [vp, vp, vp, C.c_uint64, vp, f32, vp, vp]),
         "netmax_set_fusion": (C.c_int, [vp, i32]),
+        "netmax_set_barrier_patience": (C.c_int, [vp, i64]),
         "netmax_activity": (C.c_int, [C.c_int32, vp, vp, vp, vp]),
         "netmax_mean_times": (C.c_int, [C.c_int32, vp, vp, vp, vp, C.POINTER(C.c_double)]),
         "netmax_set_activity": (C.c_int, [vp, vp]),
@@ -243,6 +244,10 @@ def netmax_run(ctx, first_iter: int, n_iters: int, peers, use_graph: bool = Fals
 
 def netmax_set_fusion(ctx, on: bool):
     _check(load().netmax_set_fusion(ctx, int(bool(on))), ctx)
+
+
+def netmax_set_barrier_patience(ctx, polls: int):
+    _check(load().netmax_set_barrier_patience(ctx, polls), ctx)
 
 
 def netmax_activity(t: np.ndarray, P: np.ndarray, adj: Optional[np.ndarray] = None) -> np.ndarray:

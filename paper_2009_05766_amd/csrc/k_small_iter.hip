@@ -33,7 +33,6 @@ constexpr int SI_MAX_OUT = 32;              // classes
 constexpr int SI_LDS_LIMIT = 150 * 1024;
 constexpr int SI_BURST = 8;                 // loads a thread has in flight while it fills LDS
 constexpr int SI_UPD = 4;                   // vectors of x_peer and v per thread and pass of the update
-constexpr long long SI_SPIN_LIMIT = 1ll << 24;   // polls of the barrier counter before a workgroup gives up
 
 struct SmallIterArgs {
     int M, B, din, dout;
@@ -49,6 +48,7 @@ struct SmallIterArgs {
     int n_iters, grad_only;
     unsigned *barrier; unsigned barrier_base; int *fault;
     const int32_t *workers;                 // grad_only: workgroup s works for worker workers[s] at iteration iter + s (NULL: s, iter)
+    long long patience;                     // polls of the barrier counter before a workgroup gives up
 };
 
 static int small_iter_cap(int64_t dout) { return dout <= 8 ? 8 : (dout <= 16 ? 16 : SI_MAX_OUT); }
@@ -61,8 +61,8 @@ static size_t small_iter_lds(int B, int din, int dout, int64_t ld)
 }
 
 // All workgroups of the grid have arrived (and their stores are visible to each other) when this returns true.  A
-// workgroup that polls SI_SPIN_LIMIT times without seeing the others raises *fault and goes on, so the kernel always ends.
-__device__ __forceinline__ void grid_barrier(unsigned *counter, unsigned target, int *fault)
+// workgroup that polls `patience` times without seeing the others raises *fault and goes on, so the kernel always ends.
+__device__ __forceinline__ void grid_barrier(unsigned *counter, unsigned target, int *fault, long long patience)
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");        // this wave's stores, device wide
     __syncthreads();
@@ -70,7 +70,7 @@ __device__ __forceinline__ void grid_barrier(unsigned *counter, unsigned target,
         __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         long long polls = 0;
         while ((int)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-            if (++polls > SI_SPIN_LIMIT) {
+            if (++polls > patience) {
                 *fault = 1;
                 break;
             }
@@ -449,7 +449,7 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
         if (more) {
             request_rows(t, nxt, rf);                         // the next iteration's batch rows travel across the barrier
             if (t < p.B) yl[nxt * p.B + t] = label;
-            grid_barrier(p.barrier, p.barrier_base + (unsigned)(it + 1) * (unsigned)p.M, p.fault);
+            grid_barrier(p.barrier, p.barrier_base + (unsigned)(it + 1) * (unsigned)p.M, p.fault, p.patience);
         }
     }
 }
@@ -487,6 +487,7 @@ hipError_t launch_small_iter(hipStream_t s, const SmallIterLaunch &a, int cooper
     p.alpha = a.alpha; p.mu = a.mu; p.wd = a.wd; p.seed = a.seed; p.iter = a.iter; p.n_iters = a.n_iters;
     p.grad_only = a.grad_only; p.barrier = a.barrier; p.barrier_base = a.barrier_base; p.fault = a.fault;
     p.workers = a.grad_only ? a.workers : nullptr;
+    p.patience = a.patience;
     const unsigned groups = p.workers ? (unsigned)a.n_workers : (unsigned)a.M;
     const size_t lds = small_iter_lds(a.B, p.din, p.dout, a.ld);
     void *args[] = {&p};

@@ -98,6 +98,7 @@ struct SmallIterLaunch {
     float alpha, mu, wd; uint64_t seed; IterRef iter; int n_iters, grad_only;
     unsigned *barrier; unsigned barrier_base; int *fault;
     const int32_t *workers; int n_workers;   // grad_only: one workgroup per listed worker (device list), slot s at iteration iter + s
+    long long patience;                      // polls of the barrier counter before a workgroup gives up and raises *fault
 };
 bool small_iter_ok(int model_is_mlp, int n_layers, int bf16, int B, int64_t din, int64_t dout, int64_t ld);
 hipError_t prepare_small_iter();

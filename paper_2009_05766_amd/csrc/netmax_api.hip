@@ -70,6 +70,7 @@ struct netmax_ctx {
     unsigned *d_barrier = nullptr;            // grid-barrier counter, only ever advanced
     unsigned barrier_count = 0;               // its value once everything enqueued so far has run
     int *d_fault = nullptr;                   // raised by a workgroup that waited at the barrier in vain
+    long long barrier_patience = 1ll << 24;   // polls before it gives up (seconds; the barrier itself takes microseconds)
     // graph replay (netmax_run): one captured iteration per direction of the parameter ping-pong
     float *x_first = nullptr;                 // the buffer bound as x_a: decides which graph an iteration uses
     uint64_t *d_iter = nullptr;               // device cell holding the iteration number of the next replay
@@ -539,6 +540,7 @@ static SmallIterLaunch small_launch(netmax_ctx *ctx, const IterRef &iter, int n_
     a.grad_only = grad_only ? 1 : 0;
     a.barrier = ctx->d_barrier; a.barrier_base = ctx->barrier_count; a.fault = ctx->d_fault;
     a.workers = nullptr; a.n_workers = 0;
+    a.patience = ctx->barrier_patience;
     return a;
 }
 
@@ -1012,6 +1014,17 @@ extern "C" int netmax_consensus_dist_static(int32_t M, int64_t D, int64_t ld, co
     if (rc != NETMAX_OK) return rc;
     launch_consensus((hipStream_t)stream, M, D, ld, x_dev, partial, cd_dev);
     return check_launch(nullptr, "consensus (static scratch)");
+}
+
+extern "C" int netmax_set_barrier_patience(netmax_ctx *ctx, int64_t polls)
+{
+    if (!ctx) return NETMAX_EINVAL;
+    if (polls < 0) return fail(ctx, NETMAX_EINVAL, "polls must be >= 0");
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->barrier_patience = polls;
+    if (ctx->d_fault) HIP_TRY(ctx, hipMemset(ctx->d_fault, 0, sizeof(int)));
+    return NETMAX_OK;
 }
 
 extern "C" const float *netmax_params(const netmax_ctx *ctx) { return ctx ? ctx->x_cur : nullptr; }

@@ -797,3 +797,34 @@ def test_small_model_iterations_in_one_kernel(over, T):
         oracle.set_threads(1)
         for g in (calls, one, graph):
             g.close()
+
+
+@pytest.mark.gpu
+def test_barrier_that_gives_up_is_reported():
+    """The failure path of the device-wide barrier, forced from the host: with a patience of zero polls every
+    workgroup that is not the last to arrive gives up at once, raises the fault flag and goes on, so the launch ends
+    by itself; the next consensus distance reports a device error instead of a number.  With the patience restored
+    (which clears the flag) a fresh context's run matches the individual entry points again."""
+    import paper_2009_05766_amd as nm
+    w = workload("cfg1")
+    inp = inputs_of(w)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        bad, good, calls = make_gpu(w, inp), make_gpu(w, inp), make_gpu(w, inp)
+        nm.netmax_set_barrier_patience(bad.ctx, 0)
+        bad.run(0, 40)
+        side.synchronize()
+        with pytest.raises(nm.NetmaxError) as e:
+            bad.consensus_dist()
+        assert e.value.code == nm.NETMAX_EDEVICE
+        nm.netmax_set_barrier_patience(bad.ctx, 1 << 24)      # clears the flag; the parameters stay what they are
+        assert np.isfinite(bad.consensus_dist())
+        nm.netmax_set_barrier_patience(good.ctx, 1 << 24)
+        good.run(0, 40)
+        for it in range(40):
+            calls.step(it)
+        side.synchronize()
+        assert np.array_equal(good.get("x").cpu().numpy(), calls.get("x").cpu().numpy())
+        assert good.consensus_dist() == calls.consensus_dist()
+        for g in (bad, good, calls):
+            g.close()

@@ -51,7 +51,7 @@ MUTANTS = [
     ("test_oracle_grad.py", C, "for (size_t k = 0; k < n; ++k) r[k] = opnd(x[k], rb);", "for (size_t k = 0; k < n; ++k) r[k] = x[k];"),
     ("test_oracle_grad.py", C, "z_hidden[(size_t)b * dout + o] = z[o];", "z_hidden[(size_t)b * dout + o] = z[o] - (double)bias[o];"),
     ("test_oracle_grad.py", C, "z_hidden[(size_t)b * dout + o] = z[o];", "z_hidden[(size_t)b * dout + o] = z[o] > 0.0 ? z[o] : 0.0;"),
-    ("test_oracle_grad.py", C, "if (z_hidden && l + 1 < n_layers) z_hidden += (size_t)B * dout;", "if (z_hidden && l + 1 < n_layers) z_hidden += (size_t)B * din;"),
+    ("test_oracle_grad.py", C, "z_hidden[(size_t)b * dout + o] = z[o];", "z_hidden[(size_t)o * B + b] = z[o];"),
     # momentum apply + mix
     ("test_oracle_mix.py", C, "const double vn = mu * (double)v[j] + (double)g[j] + wd * (double)x[j];\n            const float vf = (float)vn;           /*",
      "const double vn = mu * (double)v[j] + (double)g[j];\n            const float vf = (float)vn;           /*"),
