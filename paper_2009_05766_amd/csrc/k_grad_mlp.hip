@@ -537,6 +537,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
     bool fast[8] = {};
     for (int l = 0; l < L; ++l) fast[l] = mfma_layer_ok(p, l);
     const bool small_last = mfma_small_last_ok(p);
+    const bool head = head_ok(p);
     auto input_of = [&](int l) {
         LayerInput in;
         in.feats = p.feats; in.row0 = p.row0; in.idx = p.idx;
@@ -557,6 +558,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
             launch_fwd_small(s, p, X);
             continue;
         }
+        if (last && head) break;         // the head kernel below starts from the last hidden activation
         FwdProblem f;
         f.in = input_of(l); f.X = X; f.M = p.M; f.woff = p.woff[l]; f.din = p.dims[l]; f.dout = p.dims[l + 1];
         f.B = p.B; f.relu = !last;
@@ -567,17 +569,25 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
         if (f.dout <= 32) launch_fwd_narrow(s, f, f.in.kind, p.M);
         else launch_gemm(s, f, f.in.kind, p.M, p.B, f.dout, f.din);
     }
-    // loss and dZ of the last layer
-    const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
-    const int64_t D = p.woff[L - 1] + p.dims[L - 1] * p.dims[L] + p.dims[L];
-    hipLaunchKernelGGL(softmax_xent_kernel, dim3(p.M), dim3(sm_threads), 0, s, p.B, p.dims[L], p.act[L], p.labels,
-                       p.row0, p.idx, p.dz[0], bf ? p.dzb[0] : nullptr, bf ? p.dzt[0] : nullptr, p.loss, p.M,
-                       p.woff[L - 1] + p.dims[L - 1] * p.dims[L], D, p.ld, G);
     bool bias_done[8] = {};
-    bias_done[L - 1] = true;         // by the kernel above
+    int cur = 0, l_top = L - 1;
+    if (head) {
+        // logits, loss, the last layer's gradient and the error of the last hidden layer (with its column sums)
+        launch_head(s, p, X, G);
+        bias_done[L - 1] = bias_done[L - 2] = true;
+        l_top = L - 2;
+        cur = 1;
+    } else {
+        // loss and dZ of the last layer
+        const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
+        const int64_t D = p.woff[L - 1] + p.dims[L - 1] * p.dims[L] + p.dims[L];
+        hipLaunchKernelGGL(softmax_xent_kernel, dim3(p.M), dim3(sm_threads), 0, s, p.B, p.dims[L], p.act[L], p.labels,
+                           p.row0, p.idx, p.dz[0], bf ? p.dzb[0] : nullptr, bf ? p.dzt[0] : nullptr, p.loss, p.M,
+                           p.woff[L - 1] + p.dims[L - 1] * p.dims[L], D, p.ld, G);
+        bias_done[L - 1] = true;     // by the kernel above
+    }
     // backward
-    int cur = 0;
-    for (int l = L - 1; l >= 0; --l) {
+    for (int l = l_top; l >= 0; --l) {
         const int64_t din = p.dims[l], dout = p.dims[l + 1];
         if (fast[l]) {
             if (fuse) launch_wgrad_mix_mfma(s, p, l, cur, *fuse);

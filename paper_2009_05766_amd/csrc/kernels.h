@@ -147,4 +147,10 @@ void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X);
 void launch_wgrad_small(hipStream_t s, const MlpPlan &p, float *G, int cur);
 void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, float *G, int cur, bool want_f32);
 
+// Last layer with at most 16 classes on fp32 operands above a hidden layer (k_grad_head.hip): one kernel from the
+// last hidden activation to the error of that layer: logits, loss, dW, db, dH and the column sums of dH.
+bool head_ok(const MlpPlan &p);
+hipError_t prepare_head();
+void launch_head(hipStream_t s, const MlpPlan &p, const float *X, float *G);
+
 }  // namespace netmax

@@ -185,6 +185,13 @@ GRAD_CASES = [
     ("cfg2", dict(M=3, batch=50, n_per_worker=80, dims=(200, 150, 130, 7))),
     ("cfg5", dict(M=3, batch=37, n_per_worker=60, dims=(300, 90, 140, 40, 6))),
     ("cfg2", dict(M=2, batch=130, n_per_worker=200, dims=(40, 50, 10))),
+    # fp32 operands, at most 16 classes above a hidden layer (everything above the last hidden activation in one
+    # kernel): batches of 16, 32 and 64 rows, 16 classes and a single one, the widest hidden layer, general layers below
+    ("cfg2", dict(M=3, batch=16, n_per_worker=40, dims=(40, 256, 16))),
+    ("cfg2", dict(M=5, batch=32, n_per_worker=50, dims=(70, 128, 3))),
+    ("cfg2", dict(M=3, batch=64, n_per_worker=90, dims=(50, 40, 192, 7))),
+    ("cfg2", dict(M=2, batch=64, n_per_worker=64, dims=(20, 1024, 1))),
+    ("cfg2", dict(M=9, batch=32, n_per_worker=33, dims=(24, 640, 10))),
 ]
 
 # Gradient tolerances, relative L2 per worker.  fp32 operands: fp32 accumulation over at most a few
