@@ -12,7 +12,7 @@
 
 namespace netmax {
 
-constexpr int TK = 32, GEMM_THREADS = 256;
+constexpr int GEMM_THREADS = 256;
 typedef float gemm_acc __attribute__((ext_vector_type(16)));
 constexpr int MAX_BATCH = 1024;
 
@@ -196,6 +196,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) grouped_gemm_kernel(Problem p)
     // k = 8 w .. 8 w + 7) and their partial tiles are added through LDS at the end, in the order of the waves.  Four
     // times as many workgroups with a quarter of the matrix instructions per step each: for few, long problems.
     constexpr int TM = SMALL ? 32 : 64, TN = SMALL ? 32 : 64;
+    constexpr int TK = SMALL ? 64 : 32;      // contraction indices per step
     __shared__ float As[TK][TM + 4];
     __shared__ float Bs[TK][TN + 4];
     __shared__ int64_t s_rows[MAX_BATCH];

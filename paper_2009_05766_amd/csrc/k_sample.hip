@@ -7,13 +7,9 @@ namespace netmax {
 
 // One thread per worker.  Row i of `thr` holds non-decreasing cumulative thresholds; the peer is the
 // number of thresholds <= u (the first m whose threshold exceeds u), clamped to the last positive entry.
-__global__ void __launch_bounds__(256) sample_peers_kernel(int M, const uint32_t *__restrict__ thr,
-                                                           const int32_t *__restrict__ last, uint64_t seed,
-                                                           IterRef iter_ref, int32_t *__restrict__ peer)
+__device__ __forceinline__ void draw_peer(int i, int M, const uint32_t *__restrict__ thr, const int32_t *__restrict__ last,
+                                          uint64_t seed, uint64_t iter, int32_t *__restrict__ peer)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= M) return;
-    const uint64_t iter = iteration_of(iter_ref);
     const uint32_t u = draw_block(seed, STREAM_PEER, 0u, (uint32_t)i, iter).a;
     const uint32_t *row = thr + (size_t)i * M;
     int lo = 0, hi = M;  // upper bound: first position with row[pos] > u
@@ -25,14 +21,19 @@ __global__ void __launch_bounds__(256) sample_peers_kernel(int M, const uint32_t
     peer[i] = lo < l ? lo : l;
 }
 
-// One thread per Philox block of four draws: idx[i][4q..4q+3] = floor(word * n_i / 2^32).
-__global__ void __launch_bounds__(256) sample_batch_kernel(int M, int B, const int32_t *__restrict__ n_rows,
-                                                           uint64_t seed, IterRef iter_ref, int32_t *__restrict__ idx)
+__global__ void __launch_bounds__(256) sample_peers_kernel(int M, const uint32_t *__restrict__ thr,
+                                                           const int32_t *__restrict__ last, uint64_t seed,
+                                                           IterRef iter_ref, int32_t *__restrict__ peer)
 {
-    const int quads = (B + 3) >> 2;
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= M * quads) return;
-    const uint64_t iter = iteration_of(iter_ref);
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    draw_peer(i, M, thr, last, seed, iteration_of(iter_ref), peer);
+}
+
+// One thread per Philox block of four draws: idx[i][4q..4q+3] = floor(word * n_i / 2^32).
+__device__ __forceinline__ void draw_batch_quad(int t, int B, int quads, const int32_t *__restrict__ n_rows, uint64_t seed,
+                                                uint64_t iter, int32_t *__restrict__ idx)
+{
     const int i = t / quads, q = t - i * quads;
     const Words4 r = draw_block(seed, STREAM_BATCH, (uint32_t)q, (uint32_t)i, iter);
     const uint32_t n = (uint32_t)n_rows[i];
@@ -41,6 +42,33 @@ __global__ void __launch_bounds__(256) sample_batch_kernel(int M, int B, const i
     for (int e = 0; e < 4; ++e) {
         const int b = 4 * q + e;
         if (b < B) idx[(size_t)i * B + b] = (int32_t)__umulhi(w[e], n);
+    }
+}
+
+__global__ void __launch_bounds__(256) sample_batch_kernel(int M, int B, const int32_t *__restrict__ n_rows,
+                                                           uint64_t seed, IterRef iter_ref, int32_t *__restrict__ idx)
+{
+    const int quads = (B + 3) >> 2;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= M * quads) return;
+    draw_batch_quad(t, B, quads, n_rows, seed, iteration_of(iter_ref), idx);
+}
+
+// Both draws of an iteration in one launch (they are independent): the first peer_blocks workgroups draw the peers,
+// the others the batch rows.
+__global__ void __launch_bounds__(256) sample_iteration_kernel(int M, const uint32_t *__restrict__ thr,
+                                                               const int32_t *__restrict__ last, int32_t *__restrict__ peer,
+                                                               int peer_blocks, int B, const int32_t *__restrict__ n_rows,
+                                                               int32_t *__restrict__ idx, uint64_t seed, IterRef iter_ref)
+{
+    const uint64_t iter = iteration_of(iter_ref);
+    if ((int)blockIdx.x < peer_blocks) {
+        const int i = blockIdx.x * blockDim.x + threadIdx.x;
+        if (i < M) draw_peer(i, M, thr, last, seed, iter, peer);
+    } else {
+        const int quads = (B + 3) >> 2;
+        const int t = ((int)blockIdx.x - peer_blocks) * blockDim.x + threadIdx.x;
+        if (t < M * quads) draw_batch_quad(t, B, quads, n_rows, seed, iter, idx);
     }
 }
 
@@ -55,6 +83,14 @@ void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uin
 {
     const int n = M * ((B + 3) / 4);
     hipLaunchKernelGGL(sample_batch_kernel, dim3((n + 255) / 256), dim3(256), 0, s, M, B, n_rows, seed, iter, idx);
+}
+
+void launch_sample_iteration(hipStream_t s, int M, const uint32_t *thr, const int32_t *last, int32_t *peer, int B,
+                             const int32_t *n_rows, int32_t *idx, uint64_t seed, const IterRef &iter)
+{
+    const int peer_blocks = (M + 255) / 256, n = M * ((B + 3) / 4);
+    hipLaunchKernelGGL(sample_iteration_kernel, dim3(peer_blocks + (n + 255) / 256), dim3(256), 0, s, M, thr, last, peer,
+                       peer_blocks, B, n_rows, idx, seed, iter);
 }
 
 // Algorithm 2, UpdateTimeVector, on a simulated network: worker i records the time t[i][m] of its iteration with

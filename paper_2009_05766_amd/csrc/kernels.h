@@ -16,6 +16,9 @@ void launch_sample_peers(hipStream_t s, int M, const uint32_t *thr, const int32_
 // Batch draws (with replacement) for every worker; n_rows[i] = shard size of worker i.
 void launch_sample_batch(hipStream_t s, int M, int B, const int32_t *n_rows, uint64_t seed, const IterRef &iter,
                          int32_t *idx);
+// both draws of an iteration in one launch
+void launch_sample_iteration(hipStream_t s, int M, const uint32_t *thr, const int32_t *last, int32_t *peer, int B,
+                             const int32_t *n_rows, int32_t *idx, uint64_t seed, const IterRef &iter);
 
 // g[i][j] = sigma * N(0,1) from Philox + Box-Muller; padding columns are zeroed.
 void launch_synth_grad(hipStream_t s, int M, int64_t D, int64_t ld, float sigma, uint64_t seed, const IterRef &iter,

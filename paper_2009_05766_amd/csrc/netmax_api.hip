@@ -505,6 +505,10 @@ static int enqueue_sample_peers(netmax_ctx *ctx, const IterRef &iter, int32_t *p
     return check_launch(ctx, "sample_peers");
 }
 
+// Peer draw and local step of one iteration inside netmax_run: perceptrons that take the kernel-by-kernel path draw
+// peers and batch rows in one launch.
+static int enqueue_draws_and_local_step(netmax_ctx *ctx, const IterRef &iter, int32_t *peers_dev);
+
 static MlpPlan make_plan(const netmax_ctx *ctx)
 {
     const netmax_config &c = ctx->cfg;
@@ -556,7 +560,8 @@ static int enqueue_small(netmax_ctx *ctx, const IterRef &iter, int n_iters, bool
 
 // fused_peers != nullptr: the matrix-core layers apply the update to their weight columns themselves (netmax_run
 // after netmax_set_fusion); enqueue_mix then covers the remaining columns only.
-static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_t *fused_peers = nullptr)
+// batch_drawn: the batch rows of this iteration are in d_idx already.
+static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_t *fused_peers = nullptr, bool batch_drawn = false)
 {
     const netmax_config &c = ctx->cfg;
     if (c.model == NETMAX_FLAT) {
@@ -565,7 +570,7 @@ static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_
         return check_launch(ctx, "synth_grad");
     }
     if (ctx->small) return enqueue_small(ctx, iter, 1, true, nullptr, false);
-    launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
+    if (!batch_drawn) launch_sample_batch(ctx->stream, c.M, c.batch, ctx->d_nrows, c.seed, iter, ctx->d_idx);
     const MlpPlan p = make_plan(ctx);
     if (fused_peers) {
         const MixArgs mx = mix_args(ctx, fused_peers);
@@ -574,6 +579,19 @@ static int enqueue_local_step(netmax_ctx *ctx, const IterRef &iter, const int32_
         launch_mlp_grad(ctx->stream, p, ctx->x_cur, ctx->g);
     }
     return check_launch(ctx, "mlp_grad");
+}
+
+static int enqueue_draws_and_local_step(netmax_ctx *ctx, const IterRef &iter, int32_t *peers_dev)
+{
+    const netmax_config &c = ctx->cfg;
+    const int32_t *fused_peers = ctx->fuse ? peers_dev : nullptr;
+    if (c.model == NETMAX_FLAT || ctx->small) {
+        const int rc = enqueue_sample_peers(ctx, iter, peers_dev);
+        return rc != NETMAX_OK ? rc : enqueue_local_step(ctx, iter, fused_peers);
+    }
+    launch_sample_iteration(ctx->stream, c.M, ctx->d_thr, ctx->d_last, peers_dev, c.batch, ctx->d_nrows, ctx->d_idx, c.seed, iter);
+    const int rc = check_launch(ctx, "sample_iteration");
+    return rc != NETMAX_OK ? rc : enqueue_local_step(ctx, iter, fused_peers, true);
 }
 
 static int enqueue_mix(netmax_ctx *ctx, const int32_t *peers_dev, bool fused = false, const IterRef &iter = IterRef{0, nullptr})
@@ -647,8 +665,7 @@ static int capture_iteration(netmax_ctx *ctx, int dir, int32_t *peers_dev)
     if (ctx->small && !ctx->fuse) {
         rc = enqueue_small(ctx, it, 1, false, peers_dev, false);
     } else {
-        rc = enqueue_sample_peers(ctx, it, peers_dev);
-        if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
+        rc = enqueue_draws_and_local_step(ctx, it, peers_dev);
         if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse, it);
     }
     if (rc == NETMAX_OK) {
@@ -693,8 +710,7 @@ extern "C" int netmax_run(netmax_ctx *ctx, uint64_t first_iter, int32_t n_iters,
     if (!use_graph) {
         for (int32_t k = 0; k < n_iters; ++k) {
             const IterRef it{first_iter + (uint64_t)k, nullptr};
-            int rc = enqueue_sample_peers(ctx, it, peers_dev);
-            if (rc == NETMAX_OK) rc = enqueue_local_step(ctx, it, ctx->fuse ? peers_dev : nullptr);
+            int rc = enqueue_draws_and_local_step(ctx, it, peers_dev);
             if (rc == NETMAX_OK) rc = enqueue_mix(ctx, peers_dev, ctx->fuse, it);
             if (rc != NETMAX_OK) return rc;
             flip(ctx);
