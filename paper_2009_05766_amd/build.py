@@ -11,7 +11,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libnetmax.so")
 
 SOURCES = ["netmax_api.hip", "k_small_iter.hip", "k_sample.hip", "k_synth_grad.hip", "k_mix.hip", "k_consensus.hip", "k_grad_mlp.hip",
-           "k_layout.hip", "k_grad_mfma.hip", "k_grad_head.hip", "policy.hip", "k_async.hip", "k_mix_subset.hip", "k_mix_synth.hip"]
+           "k_layout.hip", "k_grad_mfma.hip", "k_grad_head.hip", "k_grad_f32.hip", "policy.hip", "k_async.hip", "k_mix_subset.hip", "k_mix_synth.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",

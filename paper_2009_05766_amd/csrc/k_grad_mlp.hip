@@ -560,6 +560,10 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
             continue;
         }
         if (last && head) break;         // the head kernel below starts from the last hidden activation
+        if (fwd_f32_ok(p, l)) {
+            launch_fwd_f32(s, p, l, X);
+            continue;
+        }
         FwdProblem f;
         f.in = input_of(l); f.X = X; f.M = p.M; f.woff = p.woff[l]; f.din = p.dims[l]; f.dout = p.dims[l + 1];
         f.B = p.B; f.relu = !last;
@@ -595,6 +599,8 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
             else launch_wgrad_mfma(s, p, l, G, cur);
         } else if (l == L - 1 && small_last) {
             launch_wgrad_small(s, p, G, cur);
+        } else if (wgrad_f32_ok(p, l)) {
+            launch_wgrad_f32(s, p, l, G, p.dz[cur]);
         } else {
             WgradProblem wg;
             wg.in = input_of(l); wg.dz = p.dz[cur]; wg.M = p.M; wg.woff = p.woff[l]; wg.din = din; wg.dout = dout;

@@ -150,6 +150,14 @@ void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X);
 void launch_wgrad_small(hipStream_t s, const MlpPlan &p, float *G, int cur);
 void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, float *G, int cur, bool want_f32);
 
+// Layers on fp32 operands with a batch of 32 or 64 rows and a multiple of 32 outputs (k_grad_f32.hip): forward pass
+// and weight gradient that read W / write dW exactly once with many loads in flight.
+bool fwd_f32_ok(const MlpPlan &p, int l);
+bool wgrad_f32_ok(const MlpPlan &p, int l);
+hipError_t prepare_f32_layers();
+void launch_fwd_f32(hipStream_t s, const MlpPlan &p, int l, const float *X);
+void launch_wgrad_f32(hipStream_t s, const MlpPlan &p, int l, float *G, const float *dz);
+
 // Last layer with at most 16 classes on fp32 operands above a hidden layer (k_grad_head.hip): one kernel from the
 // last hidden activation to the error of that layer: logits, loss, dW, db, dH and the column sums of dH.
 bool head_ok(const MlpPlan &p);

@@ -348,6 +348,7 @@ extern "C" int netmax_init(netmax_ctx **out, const netmax_config *cfg)
         INIT_TRY(hipMalloc(&ctx->d_loss, M * sizeof(float)));
         INIT_TRY(hipMalloc(&ctx->d_flag, sizeof(int32_t)));
         INIT_TRY(prepare_head());
+        INIT_TRY(prepare_f32_layers());
         ctx->small = small_iter_ok(1, cfg->n_layers, cfg->gemm_in == NETMAX_BF16, cfg->batch, cfg->dims[0], cfg->dims[1], cfg->ld);
         if (ctx->small) {
             INIT_TRY(prepare_small_iter());

@@ -48,8 +48,8 @@ def _free_run(w, steps, tol, operands_bf16=False):
 
 # (workload, overrides, learning rate, steps run, tolerance, oracle operands, recorded first iteration above the tolerance)
 CASES = [
-    ("cfg2", dict(), 0.01, 400, 1e-4, False, 148),
-    ("cfg2", dict(), 0.05, 60, 1e-4, False, 13),
+    ("cfg2", dict(), 0.01, 400, 1e-4, False, 199),
+    ("cfg2", dict(), 0.05, 150, 1e-4, False, 85),
     ("cfg5", dict(n_per_worker=64, dims=(48, 32, 16, 10), batch=16), 0.01, 250, 2e-2, False, 84),
     ("cfg5", dict(n_per_worker=64, dims=(48, 32, 16, 10), batch=16), 0.05, 60, 2e-2, False, 14),
     ("cfg5", dict(M=8, n_per_worker=512, dims=(3072, 256, 128, 10)), 0.05, 50, 2e-2, False, 14),

@@ -175,9 +175,11 @@ def test_cfg2_full_shape_full_T_in_windows():
         gpu.step(it)
         assert np.array_equal(gpu.peers.cpu().numpy(), o.step(it)), it
         where, closest = relu_disagreements(gpu, Z)
-        # from identical state only summation order separates the two sides; later in a window the drift a first
-        # dispute caused (about 1e-3 of the unit's pre-activation) can dispute further decisions of that unit
-        assert closest < (1e-5 if it % K == 0 else 1e-2), (it, closest)
+        # until a decision of this window has been disputed only summation order separates the two sides (exactly
+        # so in the window's first iteration, plus the rounding carried along afterwards); once one has, the gradient
+        # it changed moves that unit's pre-activations (measured: up to 1.3e-2 of the layer's rms within a window)
+        # and can dispute further decisions of that unit
+        assert closest < (1e-5 if it % K == 0 else (1e-4 if count == 0 else 5e-2)), (it, closest, count)
         disputed[1] |= set(where[0][:, 2].tolist())
         count += len(where[0])
         if (it + 1) % K == 0:

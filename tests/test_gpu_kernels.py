@@ -192,6 +192,14 @@ GRAD_CASES = [
     ("cfg2", dict(M=3, batch=64, n_per_worker=90, dims=(50, 40, 192, 7))),
     ("cfg2", dict(M=2, batch=64, n_per_worker=64, dims=(20, 1024, 1))),
     ("cfg2", dict(M=9, batch=32, n_per_worker=33, dims=(24, 640, 10))),
+    # fp32 operands, batch 32 / 64, outputs a multiple of 32 (the streaming forward and weight-gradient kernels): input
+    # from the data and from an activation, a ragged last strip of features, an input width or a weight offset that
+    # only the weight-gradient kernel accepts, a single step of the contraction, more column blocks than waves
+    ("cfg2", dict(M=3, batch=64, n_per_worker=90, dims=(40, 64, 96, 10))),
+    ("cfg2", dict(M=5, batch=32, n_per_worker=40, dims=(50, 32, 7))),
+    ("cfg2", dict(M=2, batch=64, n_per_worker=70, dims=(24, 30, 64, 10))),
+    ("cfg2", dict(M=3, batch=32, n_per_worker=32, dims=(8, 320, 32, 4))),
+    ("cfg2", dict(M=2, batch=64, n_per_worker=100, dims=(1000, 64, 10))),
 ]
 
 # Gradient tolerances, relative L2 per worker.  fp32 operands: fp32 accumulation over at most a few
