@@ -38,7 +38,7 @@ __device__ __forceinline__ const float *input_row(const LayerF32Args &p, int g, 
     return p.gather ? p.feats + (p.row0[g] + p.idx[(size_t)g * p.B + b]) * p.din : p.act + ((size_t)g * p.B + b) * p.din;
 }
 
-// RT: 32-row tiles of the batch (1 or 2).  Grid: (dout / 32, workers).
+// RT: 32-row tiles of the batch (1 or 2).  Grid: grouped_grid(workers, dout / 32).
 template <int RT>
 __global__ void __launch_bounds__(F32_THREADS) fwd_f32_kernel(LayerF32Args p)
 {
@@ -46,28 +46,40 @@ __global__ void __launch_bounds__(F32_THREADS) fwd_f32_kernel(LayerF32Args p)
     // in the loop: [wave][2][F32_KS][32] staging of W; afterwards [wave][32 RT][33] partial tiles
     const int t = threadIdx.x, lane = t & 63, row = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int g = blockIdx.y;
-    const int64_t col0 = (int64_t)blockIdx.x * F32_COLS;
+    int g;
+    unsigned cblk;
+    if (!decode_group(blockIdx.x, (unsigned)(p.dout / F32_COLS), p.M, g, cblk)) return;      // a worker's blocks share an XCD (its A)
+    const int64_t col0 = (int64_t)cblk * F32_COLS;
     float *stage = f32_smem + wave * (2 * F32_KS * F32_COLS);
     const float bias = p.X[tiled_offset(p.M, g, p.woff + p.din * p.dout + col0 + (t & 31))];     // for the end; requested first
-    const float *arow[RT];
-#pragma unroll
-    for (int i = 0; i < RT; ++i) arow[i] = input_row(p, g, 32 * i + row) + 4 * half;
     const int kr = lane >> 3, c4 = (lane & 7) * 4;               // this lane's piece of a staged W block
     const int64_t wcol = p.woff + col0 + c4;
     const int total = (int)(p.din / F32_KS);
     f32x4 fa[F32_DEPTH][RT], fw[F32_DEPTH];
-    auto request = [&](int d, int s) {
-        const int64_t k0 = (int64_t)s * F32_KS;
-#pragma unroll
-        for (int i = 0; i < RT; ++i) fa[d][i] = *reinterpret_cast<const f32x4 *>(arow[i] + k0);
-        fw[d] = *reinterpret_cast<const f32x4 *>(p.X + tiled_offset(p.M, g, wcol + (k0 + kr) * p.dout));
+    auto request_w = [&](int d, int s) {
+        fw[d] = *reinterpret_cast<const f32x4 *>(p.X + tiled_offset(p.M, g, wcol + ((int64_t)s * F32_KS + kr) * p.dout));
     };
     // this wave's steps are wave, wave + 8, ...: n_mine of them.  Requests beyond the last one repeat it (in bounds, never
     // used), so that the loop over whole groups of F32_DEPTH steps has no branch and waits for exactly the loads it uses.
     const int n_mine = wave < total ? (total - wave + F32_WAVES - 1) / F32_WAVES : 0;
     const int s_last = wave + F32_WAVES * (n_mine - 1);
-    auto request_clamped = [&](int d, int s) { request(d, s < s_last ? s : s_last); };
+    // the first pieces of W do not wait for the batch-row numbers that the addresses of A depend on
+    if (n_mine > 0) {
+#pragma unroll
+        for (int d = 0; d < F32_DEPTH; ++d) request_w(d, wave + F32_WAVES * d < s_last ? wave + F32_WAVES * d : s_last);
+    }
+    const float *arow[RT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i) arow[i] = input_row(p, g, 32 * i + row) + 4 * half;
+    auto request_a = [&](int d, int s) {
+#pragma unroll
+        for (int i = 0; i < RT; ++i) fa[d][i] = *reinterpret_cast<const f32x4 *>(arow[i] + (int64_t)s * F32_KS);
+    };
+    auto request_clamped = [&](int d, int s) {
+        const int sc = s < s_last ? s : s_last;
+        request_a(d, sc);
+        request_w(d, sc);
+    };
     f32x16 acc[RT];
 #pragma unroll
     for (int i = 0; i < RT; ++i)
@@ -87,7 +99,7 @@ __global__ void __launch_bounds__(F32_THREADS) fwd_f32_kernel(LayerF32Args p)
     };
     if (n_mine > 0) {
 #pragma unroll
-        for (int d = 0; d < F32_DEPTH; ++d) request_clamped(d, wave + F32_WAVES * d);
+        for (int d = 0; d < F32_DEPTH; ++d) request_a(d, wave + F32_WAVES * d < s_last ? wave + F32_WAVES * d : s_last);
         int done = 0;
         for (; done + F32_DEPTH <= n_mine; done += F32_DEPTH) {
 #pragma unroll
@@ -125,7 +137,7 @@ static size_t fwd_f32_lds(int RT)
     return sizeof(float) * (stage > part ? stage : part);
 }
 
-// HB = batch / 2: values of the A^T strip per lane.  Grid: (ceil(din / 32), workers, ceil(dout / (32 * 4 * WG32_TILES)));
+// HB = batch / 2: values of the A^T strip per lane.  Grid: grouped_grid(workers, ceil(din / 32) * ceil(dout / (32 * 4 * WG32_TILES)));
 // a wave takes WG32_TILES 32 x 32 blocks of dW, four blocks apart, with the same strip of A^T.
 constexpr int WG32_THREADS = 256, WG32_WAVES = WG32_THREADS / 64, WG32_TILES = 2;
 template <int HB, bool GATHER>
@@ -133,11 +145,14 @@ __global__ void __launch_bounds__(WG32_THREADS) wgrad_f32_kernel(LayerF32Args p)
 {
     const int t = threadIdx.x, lane = t & 63, col = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int g = blockIdx.y;
     const int nct = (int)(p.dout / F32_COLS);
-    const int ct0 = (int)blockIdx.z * (WG32_WAVES * WG32_TILES) + wave;
+    const unsigned groups = (unsigned)((nct + WG32_WAVES * WG32_TILES - 1) / (WG32_WAVES * WG32_TILES));
+    int g;
+    unsigned local;
+    if (!decode_group(blockIdx.x, (unsigned)((p.din + 31) / 32) * groups, p.M, g, local)) return;   // a worker's blocks share an XCD (its dZ)
+    const int ct0 = (int)(local % groups) * (WG32_WAVES * WG32_TILES) + wave;
     if (ct0 >= nct) return;
-    const int64_t f0 = (int64_t)blockIdx.x * 32;
+    const int64_t f0 = (int64_t)(local / groups) * 32;
     const int64_t feat = f0 + col < p.din ? f0 + col : p.din - 1;       // rows beyond din repeat the last one and are not stored
     const float *zbase = p.dz + ((size_t)g * p.B + half) * p.dout + col;
     float a[HB], b[HB];
@@ -190,7 +205,7 @@ static LayerF32Args layer_f32_args(const MlpPlan &p, int l, const float *X, floa
 
 static bool f32_layer_common(const MlpPlan &p, int l)
 {
-    return !p.bf16 && (p.B == 32 || p.B == 64) && p.dims[l + 1] % F32_COLS == 0 && p.M <= 65535;
+    return !p.bf16 && (p.B == 32 || p.B == 64) && p.dims[l + 1] % F32_COLS == 0;
 }
 
 // The forward kernel reads A and W with 128-bit loads: rows of A and the pieces of W must start at multiples of 16 bytes.
@@ -213,7 +228,7 @@ hipError_t prepare_f32_layers()
 void launch_fwd_f32(hipStream_t s, const MlpPlan &p, int l, const float *X)
 {
     const LayerF32Args a = layer_f32_args(p, l, X, nullptr, nullptr);
-    const dim3 grid((unsigned)(a.dout / F32_COLS), (unsigned)p.M), block(F32_THREADS);
+    const dim3 grid(grouped_grid(p.M, (unsigned)(a.dout / F32_COLS))), block(F32_THREADS);
     if (p.B == 32) hipLaunchKernelGGL(fwd_f32_kernel<1>, grid, block, fwd_f32_lds(1), s, a);
     else hipLaunchKernelGGL(fwd_f32_kernel<2>, grid, block, fwd_f32_lds(2), s, a);
 }
@@ -223,7 +238,7 @@ void launch_wgrad_f32(hipStream_t s, const MlpPlan &p, int l, float *G, const fl
     const LayerF32Args a = layer_f32_args(p, l, nullptr, G, dz);
     const int nct = (int)(a.dout / F32_COLS);
     const int per_group = WG32_WAVES * WG32_TILES;
-    const dim3 grid((unsigned)((a.din + 31) / 32), (unsigned)p.M, (unsigned)((nct + per_group - 1) / per_group)), block(WG32_THREADS);
+    const dim3 grid(grouped_grid(p.M, (unsigned)((a.din + 31) / 32) * (unsigned)((nct + per_group - 1) / per_group))), block(WG32_THREADS);
     if (p.B == 32) {
         if (a.gather) hipLaunchKernelGGL((wgrad_f32_kernel<16, true>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((wgrad_f32_kernel<16, false>), grid, block, 0, s, a);

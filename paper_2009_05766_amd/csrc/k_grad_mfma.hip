@@ -40,24 +40,6 @@ __device__ __forceinline__ size_t tiled_offset_fast(int M, int i, int64_t j)
 
 __device__ __forceinline__ int d_row(int lane, int v) { return 4 * (lane >> 5) + (v & 3) + 8 * (v >> 2); }
 
-// Workgroup id -> (worker, block inside the worker's GEMM).  Workgroup ids are dealt round-robin to the 8
-// XCDs; all blocks of one worker are placed on the same XCD, next to each other, so the operand every
-// block of that worker re-reads (its activations / back-propagated errors) comes from HBM once and from
-// that XCD's L2 afterwards.  Returns false for the padding ids beyond the last worker.
-constexpr int MF_XCD = 8;
-__device__ __forceinline__ bool decode_group(unsigned bid, unsigned blocks_per_worker, int M, int &g, unsigned &local)
-{
-    const unsigned xcd = bid % MF_XCD, slot = bid / MF_XCD;
-    const unsigned round = slot / blocks_per_worker;
-    local = slot - round * blocks_per_worker;
-    g = (int)(round * MF_XCD + xcd);
-    return g < M;
-}
-static unsigned grouped_grid(int M, unsigned blocks_per_worker)
-{
-    return (unsigned)((M + MF_XCD - 1) / MF_XCD * MF_XCD) * blocks_per_worker;
-}
-
 // Position (in bf16 elements) of the 16-byte unit u of row n in an operand tile whose units are permuted
 // inside each row by the row's 16-block index.  The forward kernel writes its weight tile four rows apart per
 // lane (rows 4 nq + e); without the permutation those 8-byte writes meet only four bank groups (8-way

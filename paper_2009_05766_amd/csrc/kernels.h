@@ -108,6 +108,24 @@ hipError_t prepare_small_iter();
 int small_iter_max_resident(int B, int64_t din, int64_t dout, int64_t ld);
 hipError_t launch_small_iter(hipStream_t s, const SmallIterLaunch &a, int cooperative);
 
+// Workgroup id -> (worker, block inside the worker's GEMM).  Workgroup ids are dealt round-robin to the 8
+// XCDs; all blocks of one worker are placed on the same XCD, next to each other, so the operand every
+// block of that worker re-reads (its activations / back-propagated errors) comes from HBM once and from
+// that XCD's L2 afterwards.  Returns false for the padding ids beyond the last worker.
+constexpr int MF_XCD = 8;
+__device__ __forceinline__ bool decode_group(unsigned bid, unsigned blocks_per_worker, int M, int &g, unsigned &local)
+{
+    const unsigned xcd = bid % MF_XCD, slot = bid / MF_XCD;
+    const unsigned round = slot / blocks_per_worker;
+    local = slot - round * blocks_per_worker;
+    g = (int)(round * MF_XCD + xcd);
+    return g < M;
+}
+inline unsigned grouped_grid(int M, unsigned blocks_per_worker)
+{
+    return (unsigned)((M + MF_XCD - 1) / MF_XCD * MF_XCD) * blocks_per_worker;
+}
+
 // Per-worker MLP / softmax-regression gradient (grouped GEMMs).
 struct MlpPlan {
     int M, n_layers, B;
