@@ -97,8 +97,10 @@ def cpu_baseline(w, inp, budget_s: float = 12.0):
             "all_threads": {"value": w.M / (dt_mt * scale), "cores": threads, "iterations": iters_mt}}
 
 
-def measure(w, steps, warmup, mode, fuse, copy_probe):
-    """One workload: inputs to HBM, warm-up, then `steps` timed iterations.  -> (result dict, inputs)."""
+def measure(w, steps, warmup, mode, fuse, copy_probe, with_fused_variant=False):
+    """One workload: inputs to HBM, warm-up, then `steps` timed iterations.  -> (result dict, inputs).
+    with_fused_variant: where the library has one (flat models, perceptrons on the matrix-core kernels), also time
+    the same number of iterations through netmax_run with netmax_set_fusion on (reported beside the result)."""
     import numpy as np
     import torch
     import paper_2009_05766_amd as nm
@@ -158,6 +160,23 @@ def measure(w, steps, warmup, mode, fuse, copy_probe):
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
 
+    fused_variant = None
+    if with_fused_variant and not fuse and (w.model == "flat" or w.gemm_in == "bf16"):
+        try:
+            nm.netmax_set_fusion(gpu.ctx, True)
+        except nm.NetmaxError:
+            pass                                   # a perceptron none of whose layers runs on the matrix-core kernels
+        else:
+            first = warmup + K_ev + 4 + K
+            gpu.run(first, 4)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            gpu.run(first + 4, K)
+            torch.cuda.synchronize()
+            wall_fused = time.perf_counter() - t1
+            nm.netmax_set_fusion(gpu.ctx, False)
+            fused_variant = {"value": w.M * K / wall_fused, "ms_per_step": wall_fused * 1e3 / K, "launch": "run+fused"}
+
     ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in ev])   # sample, grad, mix
     ms_sample, ms_grad, ms_mix = ms.mean(axis=0)
     cd1 = gpu.consensus_dist()
@@ -182,6 +201,8 @@ def measure(w, steps, warmup, mode, fuse, copy_probe):
            "phase_ms": {"sample_peers": float(ms_sample), "local_step": float(ms_grad), "mix": float(ms_mix)},
            "consensus_distance": {"before": cd0, "after": cd1},
            "roofline": roofline}
+    if fused_variant:
+        out["fused_variant"] = fused_variant
     gpu.close()
     del gpu
     torch.cuda.set_stream(torch.cuda.default_stream())
@@ -219,7 +240,7 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     w = workload(args.workload)
-    out, inp = measure(w, args.steps, args.warmup, args.mode, args.fuse, args.copy_probe)
+    out, inp = measure(w, args.steps, args.warmup, args.mode, args.fuse, args.copy_probe, with_fused_variant=not args.no_per_config)
     if out is None:
         return 2
     if not args.no_per_config:
@@ -230,12 +251,14 @@ def main() -> int:
             if name == w.name:
                 continue
             small = name in ("cfg1", "cfg2")
-            o, _ = measure(workload(name), 400 if small else 40, 20 if small else 5, "run", False, 0)
+            o, _ = measure(workload(name), 400 if small else 40, 20 if small else 5, "run", False, 0, with_fused_variant=True)
             per[name] = {"workload": o["config"]["workload"], "value": o["value"], "unit": o["unit"], "steps": o["steps"],
                          "us_per_step": o["ms_per_step"] * 1e3,
                          "phase_us": {k: v * 1e3 for k, v in o["phase_ms"].items()},
                          "mix_roofline_frac": o["roofline"]["frac"], "mix_achieved_GBs": o["roofline"]["achieved"],
                          "dtype": o["dtype"], "launch": o["config"]["launch"]}
+            if "fused_variant" in o:
+                per[name]["fused_variant"] = o["fused_variant"]
         out["per_config"] = per
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
