@@ -12,7 +12,10 @@
 //
 // Arithmetic: fp32, fixed order.  Forward: eight lanes share a batch row, lane s takes the features k = s, s + 8, ...
 // in increasing order, the eight partial sums are added in halves.  Weight gradient: one thread per four features
-// and four classes, batch rows in increasing order.
+// and four classes, batch rows in increasing order.  Shapes that tile (at most 16 classes, a batch of 16, 32 or 64
+// rows, features a multiple of 256 / (batch / 16)) take both products on v_mfma_f32_16x16x4_f32 instead (exact fp32 products, fp32
+// accumulation; lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16] and receives D[4 (l / 16) + v][l % 16]): the
+// vector units are then left with the softmax and the update.
 //
 // The kernel lives on latency, so little is waited for that could have been asked for earlier: the peer's row and
 // the own momentum are requested before the gradient is computed and used after it; the draws of the NEXT iteration
@@ -51,12 +54,25 @@ struct SmallIterArgs {
     long long patience;                     // polls of the barrier counter before a workgroup gives up
 };
 
-static int small_iter_cap(int64_t dout) { return dout <= 8 ? 8 : (dout <= 16 ? 16 : SI_MAX_OUT); }
+// The matrix-instruction form of the two products: classes padded to one 16-wide tile, 16-row tiles of the batch, the
+// four waves split the features of the forward pass evenly in groups of 64 (no bounds test in any loop).
+static bool small_iter_mm(int B, int64_t din, int64_t dout)
+{
+    return dout <= 16 && (B == 16 || B == 32 || B == 64) && din % (256 / (B / 16)) == 0;     // every wave's part: whole groups of 64 features
+}
+static int small_iter_cap(int B, int64_t din, int64_t dout)
+{
+    if (small_iter_mm(B, din, dout)) return 16;
+    return dout <= 8 ? 8 : (dout <= 16 ? 16 : SI_MAX_OUT);
+}
+constexpr int SI_MM_PAD = 4;                // floats behind a batch row in that form: sixteen rows read together meet all banks
+constexpr int SI_MM_PART = 64 * 16;         // floats of partial logits: (parts of the features) x (batch rows) = 64 rows of 16
 
 static size_t small_iter_lds(int B, int din, int dout, int64_t ld)
 {
-    const size_t pitch = (size_t)din + SI_SPLIT, cap = (size_t)small_iter_cap(dout);
-    return (2 * (size_t)ld + ((size_t)din + 1) * (cap + 4) + (size_t)B * pitch + (size_t)B * cap + (size_t)B) * sizeof(float) +
+    const bool mm = small_iter_mm(B, din, dout);
+    const size_t pitch = (size_t)din + (mm ? SI_MM_PAD : SI_SPLIT), cap = (size_t)small_iter_cap(B, din, dout);
+    return (2 * (size_t)ld + ((size_t)din + 1) * (cap + 4) + (size_t)B * pitch + (size_t)B * cap + (size_t)B + (mm ? SI_MM_PART : 0)) * sizeof(float) +
            (4 * (size_t)B + 2) * sizeof(int32_t);
 }
 
@@ -110,9 +126,13 @@ __device__ __forceinline__ int opaque(int v)
     return v;
 }
 
-template <int CAP>                          // classes the unrolled loops cover: dout <= CAP, CAP in {8, 16, 32}
+// CAP: classes the unrolled loops cover: dout <= CAP, CAP in {8, 16, 32}.  RT > 0: the two products on matrix
+// instructions, RT = batch / 16 tiles of batch rows (CAP = 16, shapes accepted by small_iter_mm()).
+template <int CAP, int RT = 0>
 __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(SmallIterArgs p)
 {
+    constexpr bool MM = RT > 0;
+    static_assert(!MM || CAP == 16, "the matrix-instruction form pads the classes to one 16-wide tile");
     extern __shared__ __attribute__((aligned(16))) unsigned char si_smem[];
     constexpr int SI_DEPTH = CAP <= 16 ? 4 : 2;               // steps of an inner product whose LDS reads are in flight together
     constexpr int OWN = CAP / SI_SPLIT;                       // classes a lane owns after the reduction of a row
@@ -121,7 +141,7 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
     const int t0 = threadIdx.x;
     const int i = p.workers ? p.workers[blockIdx.x] : (int)blockIdx.x;
     if ((unsigned)i >= (unsigned)p.M) return;
-    const int pitch = p.din + SI_SPLIT;
+    const int pitch = p.din + (MM ? SI_MM_PAD : SI_SPLIT);
     float *xl = reinterpret_cast<float *>(si_smem);           // [ld]  the worker's parameters (W row-major [din][dout], b)
     float *gl = xl + p.ld;                                    // [ld]  its gradient
     float *wp = gl + p.ld;                                    // [din + 1][WP] W and then b with rows padded by zeros to
@@ -129,7 +149,8 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
     float *dz = wp + ((size_t)p.din + 1) * WP;                // [B][CAP], zeros beyond dout (16-byte aligned rows)
     float *xs = dz + (size_t)p.B * CAP;                       // [B][pitch] batch rows
     float *lb = xs + (size_t)p.B * pitch;                     // [B] per-row loss
-    int32_t *ib = reinterpret_cast<int32_t *>(lb + p.B);      // [2][B] batch rows (shard-local) of this and the next iteration
+    float *part = lb + p.B;                                   // MM: [parts of the features][B][16] partial logits
+    int32_t *ib = reinterpret_cast<int32_t *>(part + (MM ? SI_MM_PART : 0));   // [2][B] batch rows (shard-local) of this and the next iteration
     int32_t *yl = ib + 2 * p.B;                               // [2][B] their labels
     int32_t *cnt = yl + 2 * p.B;                              // [2] thresholds of the peer draw that are <= u
     const uint64_t iter0 = iteration_of(p.iter) + (p.workers ? (uint64_t)blockIdx.x : 0ull);
@@ -227,6 +248,7 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
         wp[(size_t)k * WP + p.dout + (q - k * (CAP - p.dout))] = 0.0f;
     }
     if (t < p.B) yl[t] = label;
+    for (int64_t j = p.D + t; j < p.ld; j += SI_THREADS) gl[j] = 0.0f;     // the padding behind the gradient: written here only
 
     for (int it = 0; it < p.n_iters; ++it) {
         const uint64_t iter = iter0 + (uint64_t)it;
@@ -262,6 +284,60 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
             if (t == 0) cnt[nxt] = 0;
             label = draw_batch(t, iter + 1, nxt);
         }
+        if constexpr (MM) {
+            // ---- forward on matrix instructions: wave = (16-row tile of the batch, part of the features); four steps
+            // of sixteen features are read from LDS together, then multiplied
+            const int t = opaque(t0);
+            const int lane = t & 63, wave = t >> 6, r = lane & 15, q = lane >> 4;
+            constexpr int BT = MM ? RT : 1, KP = 4 / BT;
+            const int KW = p.din / KP, rt = wave % BT, kp = wave / BT;
+            const float *xrow = xs + (size_t)(16 * rt + r) * pitch + kp * KW + 4 * q;
+            const float *wcol = wp + (size_t)(kp * KW + 4 * q) * WP + r;
+            f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int k0 = 0; k0 < KW; k0 += 64) {
+                f32x4 a[4];
+                float b[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    a[u] = *reinterpret_cast<const f32x4 *>(xrow + k0 + 16 * u);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) b[u][j] = wcol[(size_t)(k0 + 16 * u + j) * WP];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][j], b[u][j], acc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) part[(size_t)(kp * p.B + 16 * rt + 4 * q + v) * 16 + r] = acc[v];
+            __syncthreads();
+            // ---- the parts added in order, bias, softmax, loss, dZ: sixteen lanes per batch row, one class each
+            const float *bias = wp + (size_t)p.din * WP;
+            for (int e = t; e < p.B * 16; e += SI_THREADS) {
+                const int b = e >> 4, c = e & 15;
+                float z = part[(size_t)b * 16 + c];
+#pragma unroll
+                for (int kk = 1; kk < KP; ++kk) z += part[(size_t)(kk * p.B + b) * 16 + c];
+                const bool real = c < p.dout;
+                z = real ? z + bias[c] : -INFINITY;
+                float mx = z;
+                mx = fmaxf(mx, xor_lane<1>(mx));
+                mx = fmaxf(mx, xor_lane<2>(mx));
+                mx = fmaxf(mx, xor_lane<4>(mx));
+                mx = fmaxf(mx, __shfl_xor(mx, 8, 16));
+                const float ex = real ? expf(z - mx) : 0.0f;
+                float sum = ex;
+                sum += xor_lane<1>(sum);
+                sum += xor_lane<2>(sum);
+                sum += xor_lane<4>(sum);
+                sum += __shfl_xor(sum, 8, 16);
+                const int y = yl[cur * p.B + b];
+                dz[(size_t)b * CAP + c] = real ? (ex * (1.0f / sum) - (c == y ? 1.0f : 0.0f)) * invB : 0.0f;
+                if (c == y) lb[b] = logf(sum) - (z - mx);
+            }
+        } else {
         // ---- forward, softmax, loss, dZ: eight lanes per batch row; lane s adds the features s, s + 8, ... in order,
         // the lanes then add their partial sums in halves, so that each ends up owning OWN classes of the row
         {
@@ -345,6 +421,7 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
                 }
             }
         }
+        }
         __syncthreads();
         // the peer's row and the own momentum are requested before the gradient is computed and used after it
         f32x4 rxp[SI_UPD], rv[SI_UPD];
@@ -361,7 +438,43 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
         }
         if (more) count_thresholds(t, iter + 1, nxt, thr_own);
         // ---- gradient into LDS: dW[k][o] = sum_b x[b][k] dz[b][o], db[o] = sum_b dz[b][o] (batch rows in order), padding 0
-        {
+        if constexpr (MM) {
+            // a wave takes sixteen features at a time; the batch is the contraction (step s, lane group q: row 4 s + q)
+            const int t = opaque(t0);
+            const int lane = t & 63, wave = t >> 6, r = lane & 15, q = lane >> 4;
+            constexpr int STEPS = MM ? 4 * RT : 1;           // batch / 4
+            float bz[STEPS];
+#pragma unroll
+            for (int s4 = 0; s4 < STEPS; ++s4) bz[s4] = dz[(size_t)(4 * s4 + q) * CAP + r];
+            for (int kt = wave; kt < (p.din >> 4); kt += SI_THREADS / 64) {
+                float av[STEPS];
+#pragma unroll
+                for (int s4 = 0; s4 < STEPS; ++s4) av[s4] = xs[(size_t)(4 * s4 + q) * pitch + 16 * kt + r];
+                __builtin_amdgcn_sched_barrier(0);
+                f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int s4 = 0; s4 < STEPS; ++s4) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s4], bz[s4], acc, 0, 0, 0);
+                if (r < p.dout) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) gl[(size_t)(16 * kt + 4 * q + v) * p.dout + r] = acc[v];
+                }
+            }
+            if (wave == SI_THREADS / 64 - 1) {
+                // db = column sums of dZ: the same product with a row of ones in place of the features
+                f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                const float one = r == 0 ? 1.0f : 0.0f;
+#pragma unroll
+                for (int s4 = 0; s4 < STEPS; ++s4) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(one, bz[s4], acc, 0, 0, 0);
+                if (q == 0 && r < p.dout) gl[(size_t)p.din * p.dout + r] = acc[0];
+            }
+            if (wave == 0) {
+                // the loss: the rows' terms added by one wave in a fixed tree
+                float l = lane < p.B ? lb[lane] : 0.0f;
+#pragma unroll
+                for (int m2 = 32; m2 > 0; m2 >>= 1) l += __shfl_xor(l, m2);
+                if (lane == 0) p.loss[i] = l * invB;
+            }
+        } else {
             constexpr int OG = CAP / 4;                       // groups of four classes
             const int t = opaque(t0);
             const int og = t % OG, n_kg = (p.din + 3) >> 2;
@@ -399,14 +512,13 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
                         if (4 * kg + a < p.din && 4 * og + c < p.dout) gl[(size_t)(4 * kg + a) * p.dout + 4 * og + c] = acc[a][c];
             }
         }
-        for (int64_t j = p.D + t; j < p.ld; j += SI_THREADS) gl[j] = 0.0f;
-        if (t < CAP) {                                        // the bias gradient
+        if (!MM && t < CAP) {                                 // the bias gradient
             float s = 0.0f;
 #pragma unroll 8
             for (int b = 0; b < p.B; ++b) s += dz[(size_t)b * CAP + t];
             if (t < p.dout) gl[(size_t)p.din * p.dout + t] = s;
         }
-        if (t == SI_THREADS - 1) {                            // batch rows in order
+        if (!MM && t == SI_THREADS - 1) {                     // batch rows in order
             float s = 0.0f;
 #pragma unroll 8
             for (int b = 0; b < p.B; ++b) s += lb[b];
@@ -460,8 +572,13 @@ bool small_iter_ok(int model_is_mlp, int n_layers, int bf16, int B, int64_t din,
            small_iter_lds(B, (int)din, (int)dout, ld) <= (size_t)SI_LDS_LIMIT;
 }
 
-static const void *small_iter_kernel(int64_t dout)
+static const void *small_iter_kernel(int B, int64_t din, int64_t dout)
 {
+    if (small_iter_mm(B, din, dout)) {
+        if (B == 16) return reinterpret_cast<const void *>(small_softmax_iteration_kernel<16, 1>);
+        if (B == 32) return reinterpret_cast<const void *>(small_softmax_iteration_kernel<16, 2>);
+        return reinterpret_cast<const void *>(small_softmax_iteration_kernel<16, 4>);
+    }
     if (dout <= 8) return reinterpret_cast<const void *>(small_softmax_iteration_kernel<8>);
     if (dout <= 16) return reinterpret_cast<const void *>(small_softmax_iteration_kernel<16>);
     return reinterpret_cast<const void *>(small_softmax_iteration_kernel<SI_MAX_OUT>);
@@ -469,8 +586,14 @@ static const void *small_iter_kernel(int64_t dout)
 
 hipError_t prepare_small_iter()
 {
-    for (int64_t dout : {8, 16, SI_MAX_OUT}) {
-        const hipError_t e = hipFuncSetAttribute(small_iter_kernel(dout), hipFuncAttributeMaxDynamicSharedMemorySize, SI_LDS_LIMIT);
+    const void *kernels[] = {reinterpret_cast<const void *>(small_softmax_iteration_kernel<8>),
+                             reinterpret_cast<const void *>(small_softmax_iteration_kernel<16>),
+                             reinterpret_cast<const void *>(small_softmax_iteration_kernel<SI_MAX_OUT>),
+                             reinterpret_cast<const void *>(small_softmax_iteration_kernel<16, 1>),
+                             reinterpret_cast<const void *>(small_softmax_iteration_kernel<16, 2>),
+                             reinterpret_cast<const void *>(small_softmax_iteration_kernel<16, 4>)};
+    for (const void *k : kernels) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, SI_LDS_LIMIT);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -492,8 +615,8 @@ hipError_t launch_small_iter(hipStream_t s, const SmallIterLaunch &a, int cooper
     const size_t lds = small_iter_lds(a.B, p.din, p.dout, a.ld);
     void *args[] = {&p};
     if (cooperative)
-        return hipLaunchCooperativeKernel(small_iter_kernel(a.dout), dim3(groups), dim3(SI_THREADS), args, (unsigned)lds, s);
-    return hipLaunchKernel(small_iter_kernel(a.dout), dim3(groups), dim3(SI_THREADS), args, lds, s);
+        return hipLaunchCooperativeKernel(small_iter_kernel(a.B, a.din, a.dout), dim3(groups), dim3(SI_THREADS), args, (unsigned)lds, s);
+    return hipLaunchKernel(small_iter_kernel(a.B, a.din, a.dout), dim3(groups), dim3(SI_THREADS), args, lds, s);
 }
 
 // How many workgroups of the kernel fit on the device at once with this much LDS each (0 if unknown).
@@ -503,7 +626,7 @@ int small_iter_max_resident(int B, int64_t din, int64_t dout, int64_t ld)
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
     if (!prop.cooperativeLaunch) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, small_iter_kernel(dout), SI_THREADS,
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, small_iter_kernel(B, din, dout), SI_THREADS,
                                                      small_iter_lds(B, (int)din, (int)dout, ld)) != hipSuccess)
         return 0;
     return per_cu * prop.multiProcessorCount;
