@@ -195,12 +195,10 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
     auto request_rows = [&](int t, int buf, f32x4 (&r)[SI_BURST]) {
 #pragma unroll
         for (int e = 0; e < SI_BURST; ++e) {
-            const int q = e * SI_THREADS + t;
-            if (q < feat_units) {
-                const int b = div_magic(q, magic_row), c = q - b * row_units;
-                const float *src = shard + (size_t)ib[buf * p.B + b] * p.din;
-                if (vec_rows) r[e] = load4(src + 4 * c); else r[e][0] = src[c];
-            }
+            const int q = e * SI_THREADS + t, qc = q < feat_units ? q : 0;     // unconditional, see the update's requests
+            const int b = div_magic(qc, magic_row), c = qc - b * row_units;
+            const float *src = shard + (size_t)ib[buf * p.B + b] * p.din;
+            if (vec_rows) r[e] = load4(src + 4 * c); else r[e][0] = src[c];
         }
     };
     auto store_piece = [&](int q, const f32x4 &v) {
@@ -228,7 +226,7 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
 #pragma unroll
     for (int e = 0; e < SI_BURST; ++e) {
         const int q = e * SI_THREADS + t;
-        if (q < n_vec) rpar[e] = load4(p.x_first + tiled_offset(p.M, i, (int64_t)q * 4));
+        rpar[e] = load4(p.x_first + tiled_offset(p.M, i, (int64_t)(q < n_vec ? q : 0) * 4));
     }
     if (t < 2) cnt[t] = 0;
     int32_t label = draw_batch(t, iter0, 0);
@@ -429,11 +427,11 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
             const int t = opaque(t0);
 #pragma unroll
             for (int e = 0; e < SI_UPD; ++e) {
-                const int q = e * SI_THREADS + t;
-                if (q < n_vec) {
-                    rxp[e] = load4(Xcur + tiled_offset(p.M, m, (int64_t)q * 4));
-                    rv[e] = load4(p.V + tiled_offset(p.M, i, (int64_t)q * 4));
-                }
+                // unconditional (beyond the end: the first vector again, never used): a load under a branch is
+                // waited for where the branches join, one round trip per pair instead of one for all
+                const int q = e * SI_THREADS + t, qc = q < n_vec ? q : 0;
+                rxp[e] = load4(Xcur + tiled_offset(p.M, m, (int64_t)qc * 4));
+                rv[e] = load4(p.V + tiled_offset(p.M, i, (int64_t)qc * 4));
             }
         }
         if (more) count_thresholds(t, iter + 1, nxt, thr_own);
@@ -532,11 +530,9 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
             if (q0 > 0 && !p.grad_only) {                     // beyond what was requested ahead
 #pragma unroll
                 for (int e = 0; e < SI_UPD; ++e) {
-                    const int q = q0 + e * SI_THREADS + t;
-                    if (q < n_vec) {
-                        rxp[e] = load4(Xcur + tiled_offset(p.M, m, (int64_t)q * 4));
-                        rv[e] = load4(p.V + tiled_offset(p.M, i, (int64_t)q * 4));
-                    }
+                    const int q = q0 + e * SI_THREADS + t, qc = q < n_vec ? q : 0;
+                    rxp[e] = load4(Xcur + tiled_offset(p.M, m, (int64_t)qc * 4));
+                    rv[e] = load4(p.V + tiled_offset(p.M, i, (int64_t)qc * 4));
                 }
             }
 #pragma unroll
