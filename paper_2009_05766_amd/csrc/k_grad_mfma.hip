@@ -440,24 +440,32 @@ __device__ __forceinline__ void load_at_block(uint16_t (*At)[WG_PITCH], int t, i
                                               const uint16_t *a_t, const uint16_t *feats, const int64_t *row0,
                                               const int32_t *idx)
 {
+    // No load sits under a branch (one under a bounds test is waited for where the branches join: a round trip per
+    // load instead of one for all): indices past the end are clamped and what they load is not stored.
     if (feats) {
         constexpr int KC = ROWS / 8;                             // 16-byte chunks of a batch row inside the strip
-        constexpr int N = KC * 128 / MF_THREADS;                 // chunks per thread at the largest batch, all requested first
+        constexpr int N = KC * 128 / MF_THREADS;                 // chunks per thread at the largest batch
+        const int n = KC * B;
+        int kcs[N], bs[N];
+        int32_t rows[N];
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            const int c = t + q * MF_THREADS, cc = c < n ? c : n - 1;
+            kcs[q] = cc / B;
+            bs[q] = cc - kcs[q] * B;
+            rows[q] = idx[(size_t)g * B + bs[q]];                // all batch-row numbers first, then all rows
+        }
+        const uint16_t *base = feats + (size_t)row0[g] * din + r0;
         u32x4 v[N];
 #pragma unroll
-        for (int q = 0; q < N; ++q) {
-            const int c = t + q * MF_THREADS, kc = c / B, b = c - kc * B;
-            if (c < KC * B)
-                v[q] = *reinterpret_cast<const u32x4 *>(feats + (size_t)(row0[g] + idx[(size_t)g * B + b]) * din + r0 + 8 * kc);
-        }
+        for (int q = 0; q < N; ++q) v[q] = *reinterpret_cast<const u32x4 *>(base + (size_t)rows[q] * din + 8 * kcs[q]);
 #pragma unroll
         for (int q = 0; q < N; ++q) {
-            const int c = t + q * MF_THREADS, kc = c / B, b = c - kc * B;
-            if (c < KC * B) {
+            if (t + q * MF_THREADS < n) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    At[8 * kc + 2 * e][b] = (uint16_t)(v[q][e] & 0xFFFFu);
-                    At[8 * kc + 2 * e + 1][b] = (uint16_t)(v[q][e] >> 16);
+                    At[8 * kcs[q] + 2 * e][bs[q]] = (uint16_t)(v[q][e] & 0xFFFFu);
+                    At[8 * kcs[q] + 2 * e + 1][bs[q]] = (uint16_t)(v[q][e] >> 16);
                 }
             }
         }
@@ -465,10 +473,20 @@ __device__ __forceinline__ void load_at_block(uint16_t (*At)[WG_PITCH], int t, i
     }
     const int chunks_per_row = B >> 3;
     const uint16_t *a_src = a_t + ((size_t)g * din + r0) * B;
-    for (int c = t; c < ROWS * chunks_per_row; c += MF_THREADS) {
-        const int row = c / chunks_per_row, col = (c - row * chunks_per_row) * 8;
-        *reinterpret_cast<u32x4 *>(&At[row][col]) = *reinterpret_cast<const u32x4 *>(a_src + (size_t)row * B + col);
+    constexpr int N = ROWS * 16 / MF_THREADS;                    // chunks per thread at the largest batch
+    const int n = ROWS * chunks_per_row;
+    int rws[N], cols[N];
+    u32x4 v[N];
+#pragma unroll
+    for (int q = 0; q < N; ++q) {
+        const int c = t + q * MF_THREADS, cc = c < n ? c : n - 1;
+        rws[q] = cc / chunks_per_row;
+        cols[q] = (cc - rws[q] * chunks_per_row) * 8;
+        v[q] = *reinterpret_cast<const u32x4 *>(a_src + (size_t)rws[q] * B + cols[q]);
     }
+#pragma unroll
+    for (int q = 0; q < N; ++q)
+        if (t + q * MF_THREADS < n) *reinterpret_cast<u32x4 *>(&At[rws[q]][cols[q]]) = v[q];
 }
 
 // STRIP: rows of W per workgroup (128 or 64), BN: columns per block step (128 or 64); waves 2 x 2, each
