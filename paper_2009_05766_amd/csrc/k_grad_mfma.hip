@@ -265,15 +265,39 @@ struct DgradOut {
     float *G; int64_t boff;       // bias gradient of the layer below: G[tile layout, boff + column]
 };
 
+// BURST: how many of the eight pieces of the activation tile a thread requests at a time (0: see below).
+template <int BURST>
 __device__ __forceinline__ void dgrad_tail(const DgradOut &o, int M, int g, int B, int64_t din, int64_t c0, int wm, int wn,
                                            int lane, int t, f32x16 (&acc)[2][2], uint16_t (*T)[ST_PITCH], float (*red)[2][64])
 {
     const int wave = 2 * wm + wn;
     // the activations under the tile (ReLU mask) come in as whole rows
+    // (all eight requested before the first is stored, rows past the batch clamped: a load under a bounds test is
+    // waited for where the branches join, one round trip per load)
+    if constexpr (BURST == 0) {
+        // one piece at a time, each under its bounds test: for the kernel whose registers are all taken by the tile
+        // (requesting the pieces together made it spill more and run 4 % slower)
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        const int chunk = t + q * MF_THREADS, r = chunk >> 4, c = (chunk & 15) * 8;
-        if (r < B) *reinterpret_cast<u32x4 *>(&T[r][c]) = *reinterpret_cast<const u32x4 *>(o.act + ((size_t)g * B + r) * din + c0 + c);
+        for (int q = 0; q < 8; ++q) {
+            const int chunk = t + q * MF_THREADS, r = chunk >> 4, c = (chunk & 15) * 8;
+            if (r < B) *reinterpret_cast<u32x4 *>(&T[r][c]) = *reinterpret_cast<const u32x4 *>(o.act + ((size_t)g * B + r) * din + c0 + c);
+        }
+    } else {
+#pragma unroll
+    for (int q0 = 0; q0 < 8; q0 += (BURST > 0 ? BURST : 8)) {
+        u32x4 mask_rows[BURST > 0 ? BURST : 1];
+#pragma unroll
+        for (int q = 0; q < BURST; ++q) {
+            const int chunk = t + (q0 + q) * MF_THREADS, r = chunk >> 4, c = (chunk & 15) * 8;
+            mask_rows[q] = *reinterpret_cast<const u32x4 *>(o.act + ((size_t)g * B + (r < B ? r : B - 1)) * din + c0 + c);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < BURST; ++q) {
+            const int chunk = t + (q0 + q) * MF_THREADS, r = chunk >> 4, c = (chunk & 15) * 8;
+            if (r < B) *reinterpret_cast<u32x4 *>(&T[r][c]) = mask_rows[q];
+        }
+    }
     }
     __syncthreads();
 #pragma unroll
@@ -407,7 +431,7 @@ __device__ __forceinline__ void dgrad_mfma_body(const DgradMfmaArgs &p)
         tile_mma_128<BK, false>(As, Bs, wm, wn, lane, acc);
     }
     __syncthreads();                 // the last step's reads of the operand tiles are done
-    dgrad_tail(p.o, p.M, g, p.B, p.din, c0, wm, wn, lane, t, acc, T, red);
+    dgrad_tail<0>(p.o, p.M, g, p.B, p.din, c0, wm, wn, lane, t, acc, T, red);
 }
 
 __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) dgrad_mfma_kernel(DgradMfmaArgs p)
@@ -700,14 +724,26 @@ __global__ void __launch_bounds__(MF_THREADS) fwd_small_mfma_kernel(FwdSmallArgs
     // W[k][n] -> Wt[n][k]: the din x dout block is contiguous in the parameter row and starts at a multiple of four
     // columns, so it is read as float4 (a float4 never straddles a layout tile)
     {
+        // eight pieces per thread are requested together (past the end: the first piece again, not stored)
         const unsigned n_w = (unsigned)(din * dout), udout = (unsigned)dout;
-#pragma unroll 2
-        for (unsigned e4 = 4u * t; e4 < n_w; e4 += 4u * MF_THREADS) {
-            const f32x4_t w = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, p.woff + e4));
+        for (unsigned base = 4u * t; base < n_w; base += 8u * 4u * MF_THREADS) {
+            f32x4_t w[8];
 #pragma unroll
-            for (unsigned c = 0; c < 4; ++c) {
-                const unsigned e = e4 + c, k = e / udout, n = e - k * udout;
-                Wt[n * pitch + k] = (uint16_t)bf16_bits(w[c]);
+            for (unsigned u = 0; u < 8; ++u) {
+                const unsigned e4 = base + u * 4u * MF_THREADS;
+                w[u] = *reinterpret_cast<const f32x4_t *>(p.X + tiled_offset(p.M, g, p.woff + (e4 < n_w ? e4 : 0u)));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (unsigned u = 0; u < 8; ++u) {
+                const unsigned e4 = base + u * 4u * MF_THREADS;
+                if (e4 < n_w) {
+#pragma unroll
+                    for (unsigned c = 0; c < 4; ++c) {
+                        const unsigned e = e4 + c, k = e / udout, n = e - k * udout;
+                        Wt[n * pitch + k] = (uint16_t)bf16_bits(w[u][c]);
+                    }
+                }
             }
         }
     }
@@ -723,8 +759,10 @@ __global__ void __launch_bounds__(MF_THREADS) fwd_small_mfma_kernel(FwdSmallArgs
             u32x4 a[8];
 #pragma unroll
             for (int s = 0; s < 8; ++s) a[s] = *reinterpret_cast<const u32x4 *>(a_ptr + k0 + 16 * s);
+            __builtin_amdgcn_sched_barrier(0);             // or the loads are interleaved with the instructions that wait for them
 #pragma unroll
             for (int s = 0; s < 8; ++s) acc = mfma_bf16(a[s], *reinterpret_cast<const u32x4 *>(b_ptr + k0 + 16 * s), acc);
+            __builtin_amdgcn_sched_barrier(0);
         }
         const int col = lane & 31;
         if (col < dout) {
@@ -750,15 +788,24 @@ __global__ void __launch_bounds__(MF_THREADS) wgrad_small_mfma_kernel(WgradSmall
     const int64_t r0 = (int64_t)strip * 128 + 32 * wave;
     const uint16_t *a_ptr = p.a_t + ((size_t)g * p.din + r0 + (lane & 31)) * p.B + 8 * (lane >> 5);
     const int n = lane & 31;
-    const uint16_t *b_ptr = p.dz_t + ((size_t)g * p.dout + n) * p.B + 8 * (lane >> 5);
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    for (int b0 = 0; b0 < p.B; b0 += 16) {
-        const u32x4 a = *reinterpret_cast<const u32x4 *>(a_ptr + b0);
-        const u32x4 b = n < p.dout ? *reinterpret_cast<const u32x4 *>(b_ptr + b0) : (u32x4){0u, 0u, 0u, 0u};
-        acc = mfma_bf16(a, b, acc);
+    // the batch is at most 128: all eight steps' operands are requested before the first product (steps past the batch
+    // and classes past dout repeat a valid address and are masked)
+    const uint16_t *b_ok = p.dz_t + ((size_t)g * p.dout + (n < p.dout ? n : 0)) * p.B + 8 * (lane >> 5);
+    const uint32_t keep = n < p.dout ? 0xFFFFFFFFu : 0u;
+    u32x4 av[8], bv[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int b0 = 16 * s < p.B ? 16 * s : 0;
+        av[s] = *reinterpret_cast<const u32x4 *>(a_ptr + b0);
+        bv[s] = *reinterpret_cast<const u32x4 *>(b_ok + b0);
     }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+        if (16 * s < p.B) acc = mfma_bf16(av[s], (u32x4){bv[s][0] & keep, bv[s][1] & keep, bv[s][2] & keep, bv[s][3] & keep}, acc);
     if (n < p.dout) {
 #pragma unroll
         for (int v = 0; v < 16; ++v)
@@ -793,22 +840,38 @@ __global__ void __launch_bounds__(MF_THREADS) dgrad_small_mfma_kernel(DgradSmall
     for (int s = 0; s < steps; ++s) {
         const int nbase = 16 * s + 8 * (lane >> 5);
         u32x4 a[2], b[2];
+        // All 32 values are requested before any is used: unconditional loads (row / class clamped into the operand,
+        // the value masked afterwards; a load under the bounds test, or selected by it, is waited for one by one).
+        uint32_t zr[2][8];
+        float xr[2][8];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = 64 * wm + 32 * i + (lane & 31);
+            const uint16_t *zrow = p.dz + ((size_t)g * p.B + (row < p.B ? row : p.B - 1)) * p.dout;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) zr[i][e] = zrow[nbase + e < p.dout ? nbase + e : 0];
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t feat = c0 + 64 * wn + 32 * j + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                xr[j][e] = p.X[tiled_offset(p.M, g, p.woff + feat * p.dout + (nbase + e < p.dout ? nbase + e : 0))];
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = 64 * wm + 32 * i + (lane & 31);
             uint32_t h[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                h[e] = (row < p.B && nbase + e < p.dout) ? p.dz[((size_t)g * p.B + row) * p.dout + nbase + e] : 0u;
+            for (int e = 0; e < 8; ++e) h[e] = zr[i][e] & ((row < p.B && nbase + e < p.dout) ? 0xFFFFu : 0u);
             a[i] = (u32x4){h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int64_t feat = c0 + 64 * wn + 32 * j + (lane & 31);
             float w[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                w[e] = nbase + e < p.dout ? p.X[tiled_offset(p.M, g, p.woff + feat * p.dout + nbase + e)] : 0.0f;
+            for (int e = 0; e < 8; ++e) w[e] = __uint_as_float(__float_as_uint(xr[j][e]) & (nbase + e < p.dout ? 0xFFFFFFFFu : 0u));
             b[j] = (u32x4){pack_bf16x2(w[0], w[1]), pack_bf16x2(w[2], w[3]), pack_bf16x2(w[4], w[5]), pack_bf16x2(w[6], w[7])};
         }
 #pragma unroll
@@ -816,7 +879,7 @@ __global__ void __launch_bounds__(MF_THREADS) dgrad_small_mfma_kernel(DgradSmall
 #pragma unroll
             for (int j = 0; j < 2; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
     }
-    dgrad_tail(p.o, p.M, g, p.B, p.din, c0, wm, wn, lane, t, acc, T, red);
+    dgrad_tail<8>(p.o, p.M, g, p.B, p.din, c0, wm, wn, lane, t, acc, T, red);
 }
 
 // ---------------------------------------------------------------------------------------------------
