@@ -11,6 +11,7 @@
 #include "bf16.h"
 #include "kernels.h"
 #include "layout.h"
+#include "softmax_xent.h"
 #include "vec.h"
 
 namespace netmax {
@@ -711,6 +712,7 @@ __global__ void __launch_bounds__(MF_THREADS) __attribute__((amdgpu_waves_per_eu
 // batch rows and reads its A operands straight from the bf16 activations.
 struct FwdSmallArgs {
     const uint16_t *a_prev; const float *X; int64_t woff; int M, B; int64_t din, dout; float *out;
+    SoftmaxArgs sm;                  // what follows the logits in the same workgroup
 };
 constexpr int SMALL_MAX_DIN = 2048;
 
@@ -771,6 +773,9 @@ __global__ void __launch_bounds__(MF_THREADS) fwd_small_mfma_kernel(FwdSmallArgs
             for (int v = 0; v < 16; ++v) p.out[((size_t)g * p.B + m0 + d_row(lane, v)) * p.dout + col] = acc[v] + bcol;
         }
     }
+    // the workgroup holds all logits of its worker: loss, dZ and the last layer's bias gradient follow at once
+    __syncthreads();
+    softmax_xent_block(p.sm, g);
 }
 
 // dW = A^T dZ with dout <= 32: one workgroup = one worker x 128 rows of W, one 32-row tile per wave;
@@ -915,12 +920,13 @@ static DgradOut dgrad_out(const MlpPlan &p, int l, int cur, float *G, bool want_
     return o;
 }
 
-void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X)
+void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X, float *G)
 {
     const int l = p.n_layers - 1;
     FwdSmallArgs a;
     a.a_prev = p.hb[l]; a.X = X; a.woff = p.woff[l]; a.M = p.M; a.B = p.B; a.din = p.dims[l]; a.dout = p.dims[l + 1];
     a.out = p.act[l + 1];
+    a.sm = softmax_args(p, G);
     const size_t lds = (size_t)32 * (a.din + 8) * sizeof(uint16_t);
     hipLaunchKernelGGL(fwd_small_mfma_kernel, dim3(p.M), dim3(MF_THREADS), lds, s, a);
 }

@@ -7,6 +7,7 @@
 #include "bf16.h"
 #include "kernels.h"
 #include "layout.h"
+#include "softmax_xent.h"
 
 #include <type_traits>
 
@@ -447,72 +448,8 @@ static void launch_gemm(hipStream_t s, const Problem &p, int kind, int groups, i
 #undef NETMAX_GEMM
 }
 
-// Softmax cross-entropy on the logits: dz = (softmax - onehot) / B and the mean loss per worker.
-// One workgroup per worker, one thread per batch row.  The workgroup then adds up the columns of dz (the
-// last layer's bias gradient, batch rows in order) and clears the padding behind the worker's gradient.
-__global__ void __launch_bounds__(1024)
-softmax_xent_kernel(int B, int64_t C, const float *__restrict__ logits, const int32_t *__restrict__ labels,
-                    const int64_t *__restrict__ row0, const int32_t *__restrict__ idx, float *__restrict__ dz,
-                    uint16_t *__restrict__ dz_bf16, uint16_t *__restrict__ dz_bf16_t, float *__restrict__ loss,
-                    int M, int64_t boff, int64_t D, int64_t ld, float *__restrict__ G)
-{
-    __shared__ float red[1024];
-    const int g = blockIdx.x, b = threadIdx.x;
-    float l = 0.0f;
-    if (b < B) {
-        const float *z = logits + ((size_t)g * B + b) * C;
-        float *d = dz + ((size_t)g * B + b) * C;
-        float mx = z[0];
-        for (int64_t o = 1; o < C; ++o) mx = fmaxf(mx, z[o]);
-        float sum = 0.0f;
-        for (int64_t o = 0; o < C; ++o) sum += expf(z[o] - mx);
-        const int y = labels[row0[g] + idx[(size_t)g * B + b]];
-        l = logf(sum) - (z[y] - mx);
-        const float inv = 1.0f / sum, invB = 1.0f / (float)B;
-        for (int64_t o = 0; o < C; ++o) {
-            const float v = (expf(z[o] - mx) * inv - (o == y ? 1.0f : 0.0f)) * invB;
-            d[o] = v;
-            if (dz_bf16) {
-                const uint16_t h = (uint16_t)bf16_bits(v);
-                dz_bf16[((size_t)g * B + b) * C + o] = h;
-                dz_bf16_t[((size_t)g * C + o) * B + b] = h;
-            }
-        }
-    }
-    red[b] = l;
-    __syncthreads();                 // also: every row of dz is written
-    for (int stride = 512; stride > 0; stride >>= 1) {
-        if (b < stride && b + stride < (int)blockDim.x) red[b] += red[b + stride];
-        __syncthreads();
-    }
-    if (b == 0) loss[g] = red[0] / (float)B;
-    for (int64_t e = b; e < ld - D; e += blockDim.x) G[tiled_offset(M, g, D + e)] = 0.0f;
-    // column sums of dz.  With few classes the rows are split over P groups of threads (rows part, part + P, ...),
-    // whose partial sums are then added in the order of the groups; otherwise one thread per column.
-    const int nt = (int)blockDim.x;
-    if (C <= nt / 2) {
-        const int c = (int)C, P = nt / c;
-        __syncthreads();             // red[0] has been read
-        if (b < c * P) {
-            const int o = b % c, part = b / c;
-            float s = 0.0f;
-            for (int r = part; r < B; r += P) s += dz[((size_t)g * B + r) * C + o];
-            red[b] = s;
-        }
-        __syncthreads();
-        if (b < c) {
-            float s = 0.0f;
-            for (int part = 0; part < P; ++part) s += red[part * c + b];
-            G[tiled_offset(M, g, boff + b)] = s;
-        }
-    } else {
-        for (int64_t o = b; o < C; o += nt) {
-            float s = 0.0f;
-            for (int r = 0; r < B; ++r) s += dz[((size_t)g * B + r) * C + o];
-            G[tiled_offset(M, g, boff + o)] = s;
-        }
-    }
-}
+// Softmax cross-entropy on the logits (softmax_xent.h): one workgroup per worker.
+__global__ void __launch_bounds__(1024) softmax_xent_kernel(SoftmaxArgs a) { softmax_xent_block(a, blockIdx.x); }
 
 // db = column sums of dZ.  One workgroup = one worker x 64 outputs; the batch rows are dealt to four groups of
 // threads (rows r, r + 4, ...), whose partial sums are added in the order of the groups.
@@ -556,7 +493,7 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
             continue;
         }
         if (last && small_last) {
-            launch_fwd_small(s, p, X);
+            launch_fwd_small(s, p, X, G);
             continue;
         }
         if (last && head) break;         // the head kernel below starts from the last hidden activation
@@ -585,10 +522,8 @@ void launch_mlp_grad(hipStream_t s, const MlpPlan &p, const float *X, float *G, 
     } else {
         // loss and dZ of the last layer
         const int sm_threads = p.B <= 64 ? 64 : (p.B <= 256 ? 256 : 1024);
-        const int64_t D = p.woff[L - 1] + p.dims[L - 1] * p.dims[L] + p.dims[L];
-        hipLaunchKernelGGL(softmax_xent_kernel, dim3(p.M), dim3(sm_threads), 0, s, p.B, p.dims[L], p.act[L], p.labels,
-                           p.row0, p.idx, p.dz[0], bf ? p.dzb[0] : nullptr, bf ? p.dzt[0] : nullptr, p.loss, p.M,
-                           p.woff[L - 1] + p.dims[L - 1] * p.dims[L], D, p.ld, G);
+        if (!small_last)             // (the last-layer forward kernel of the matrix-core path ends with it)
+            hipLaunchKernelGGL(softmax_xent_kernel, dim3(p.M), dim3(sm_threads), 0, s, softmax_args(p, G));
         bias_done[L - 1] = true;     // by the kernel above
     }
     // backward

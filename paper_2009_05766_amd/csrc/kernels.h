@@ -164,7 +164,8 @@ void launch_wgrad_mfma(hipStream_t s, const MlpPlan &p, int l, float *G, int cur
 void launch_wgrad_mix_mfma(hipStream_t s, const MlpPlan &p, int l, int cur, const MixArgs &mix);
 // Last layer with at most 32 outputs.
 bool mfma_small_last_ok(const MlpPlan &p);
-void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X);
+// also: softmax cross-entropy on the logits (loss, dZ, the last layer's bias gradient, the gradient's padding)
+void launch_fwd_small(hipStream_t s, const MlpPlan &p, const float *X, float *G);
 void launch_wgrad_small(hipStream_t s, const MlpPlan &p, float *G, int cur);
 void launch_dgrad_small(hipStream_t s, const MlpPlan &p, const float *X, float *G, int cur, bool want_f32);
 
