@@ -31,7 +31,7 @@ MIX_BYTES_MIN, MIX_BYTES_NAIVE = 20, 24
 _MIX_SOURCES = "c8b2061f1db7daaa.3f97687d5424e9a2.e54cf75f51c45279"
 MEASURED_TRAFFIC = {"cfg3": {"sources": _MIX_SOURCES, "bytes": 14338993040},
                     "cfg4": {"sources": _MIX_SOURCES, "bytes": 12802386208},
-                    "cfg5": {"sources": _MIX_SOURCES, "bytes": 10778493919}}
+                    "cfg5": {"sources": _MIX_SOURCES, "bytes": 10777505263}}
 
 
 def mix_sources_digest() -> str:
