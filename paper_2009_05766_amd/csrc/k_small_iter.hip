@@ -30,7 +30,7 @@
 
 namespace netmax {
 
-constexpr int SI_THREADS = 256;
+constexpr int SI_THREADS = 512, SI_WAVES = SI_THREADS / 64;
 constexpr int SI_SPLIT = 8;                 // lanes that share one batch row in the forward pass
 constexpr int SI_MAX_OUT = 32;              // classes
 constexpr int SI_LDS_LIMIT = 150 * 1024;
@@ -55,10 +55,10 @@ struct SmallIterArgs {
 };
 
 // The matrix-instruction form of the two products: classes padded to one 16-wide tile, 16-row tiles of the batch, the
-// four waves split the features of the forward pass evenly in groups of 64 (no bounds test in any loop).
+// the waves split the features of the forward pass evenly in groups of 64 (no bounds test in any loop).
 static bool small_iter_mm(int B, int64_t din, int64_t dout)
 {
-    return dout <= 16 && (B == 16 || B == 32 || B == 64) && din % (256 / (B / 16)) == 0;     // every wave's part: whole groups of 64 features
+    return dout <= 16 && (B == 16 || B == 32 || B == 64) && din % (64 * SI_WAVES / (B / 16)) == 0;     // every wave's part: whole groups of 64 features
 }
 static int small_iter_cap(int B, int64_t din, int64_t dout)
 {
@@ -66,7 +66,7 @@ static int small_iter_cap(int B, int64_t din, int64_t dout)
     return dout <= 8 ? 8 : (dout <= 16 ? 16 : SI_MAX_OUT);
 }
 constexpr int SI_MM_PAD = 4;                // floats behind a batch row in that form: sixteen rows read together meet all banks
-constexpr int SI_MM_PART = 64 * 16;         // floats of partial logits: (parts of the features) x (batch rows) = 64 rows of 16
+constexpr int SI_MM_PART = SI_WAVES * 16 * 16;   // floats of partial logits: one 16 x 16 tile per wave
 
 static size_t small_iter_lds(int B, int din, int dout, int64_t ld)
 {
@@ -287,7 +287,7 @@ __global__ void __launch_bounds__(SI_THREADS) small_softmax_iteration_kernel(Sma
             // of sixteen features are read from LDS together, then multiplied
             const int t = opaque(t0);
             const int lane = t & 63, wave = t >> 6, r = lane & 15, q = lane >> 4;
-            constexpr int BT = MM ? RT : 1, KP = 4 / BT;
+            constexpr int BT = MM ? RT : 1, KP = SI_WAVES / BT;
             const int KW = p.din / KP, rt = wave % BT, kp = wave / BT;
             const float *xrow = xs + (size_t)(16 * rt + r) * pitch + kp * KW + 4 * q;
             const float *wcol = wp + (size_t)(kp * KW + 4 * q) * WP + r;
